@@ -1,0 +1,159 @@
+/*
+ * quasar.h - C ABI of the int8 weight-streaming verification library for MI355X (gfx950).
+ *
+ * The library covers the memory-bound part of one verification step of
+ * self-speculative decoding with a quantised verifier: every linear layer of the
+ * target model applied to the M = gamma + 1 candidate positions, and the final
+ * vocabulary projection followed by the acceptance decision.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or retains them.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *     Calls validate their arguments on the host, enqueue their kernels on that
+ *     stream and return without waiting.  The returned status covers argument
+ *     and launch errors only, not faults that surface later on the stream.
+ *   - bf16 values are passed as uint16_t bit patterns.
+ *   - Outputs are fully overwritten.  Workspace contents need not be
+ *     initialised and are undefined afterwards.
+ *   - Shape limits (checked, QUASAR_ERR_SHAPE otherwise):
+ *         1 <= M <= 32,  K >= 64 and K % 64 == 0,  N >= 16 and N % 16 == 0,
+ *         row strides (ldx, ldy, ldh, ldw) >= the row length; ldx, ldy, ldh % 8 == 0.
+ *   - Alignment (checked, QUASAR_ERR_ALIGN otherwise): x, y, hidden, packed
+ *     weights 16 bytes; scales 8 bytes; workspace 16 bytes.
+ *   - Non-finite inputs give unspecified values but never a fault.
+ *   - Concurrent calls on different streams are safe as long as they do not
+ *     share output or workspace buffers.
+ */
+#ifndef QUASAR_H_
+#define QUASAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum quasar_status {
+    QUASAR_OK = 0,
+    QUASAR_ERR_NULL = 1,       /* a required pointer is NULL */
+    QUASAR_ERR_SHAPE = 2,      /* a size or stride is outside the documented limits */
+    QUASAR_ERR_ALIGN = 3,      /* a pointer is not aligned as documented */
+    QUASAR_ERR_WORKSPACE = 4,  /* workspace missing or smaller than quasar_workspace_bytes */
+    QUASAR_ERR_DTYPE = 5,      /* unknown quasar_dtype / quasar_path value */
+    QUASAR_ERR_HIP = 6         /* the HIP runtime reported an error at launch */
+} quasar_status;
+
+typedef enum quasar_dtype { QUASAR_F32 = 0, QUASAR_BF16 = 1 } quasar_dtype;
+
+/* Contraction variant used by quasar_w8_linear (for A/B measurements). */
+typedef enum quasar_path {
+    QUASAR_PATH_AUTO = 0,  /* library's choice by M */
+    QUASAR_PATH_VALU = 1,  /* fp32 FMA dot products on the vector ALUs, M <= 4 only */
+    QUASAR_PATH_MFMA = 2   /* bf16 matrix-core tiles */
+} quasar_path;
+
+const char *quasar_status_string(int status);
+int quasar_version(void);
+
+/* Process-wide override of the contraction variant (host argument, not thread-safe
+ * against concurrent calls).  Also settable through the environment variable
+ * QUASAR_FORCE_PATH={auto,valu,mfma}, read when the library is loaded.
+ * QUASAR_PATH_VALU with M > 4 falls back to MFMA.  Returns QUASAR_ERR_DTYPE for
+ * an unknown value. */
+int quasar_set_path(int path);
+int quasar_get_path(void);
+
+/* Bytes of the packed int8 / packed bf16 weight buffer for an [N, K] matrix.
+ * Int8: exactly one byte per parameter (the 2x footprint reduction of Sec. 3.3,
+ * "Offline Weight Preparation"); bf16: two.  0 if the shape is invalid. */
+size_t quasar_packed_bytes(int64_t N, int64_t K);
+size_t quasar_packed_bytes_bf16(int64_t N, int64_t K);
+
+/* Workspace bytes needed by quasar_*_lmhead_verify (per-workgroup argmax
+ * partials); the linear entry points need none today and accept NULL. */
+size_t quasar_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * Offline weight preparation (Sec. 3.2 Eq. 6: symmetric uniform quantisation
+ * W_int8 = Q(W, delta_w); Sec. 3.3 "Offline Weight Preparation").
+ *   w            device, [N, K] row-major, row stride ldw elements, fp32 or bf16
+ *   wq_packed    device out, quasar_packed_bytes(N, K) bytes, tile order (opaque;
+ *                quasar_unpack_weights recovers row-major codes)
+ *   scales_bf16  device out, [N] bf16: delta_n = bf16(max_k|W[n,k]| / 127)
+ * Per output row: q = clamp(rint(W / delta_n), -127, 127), rint = half to even,
+ * quotient in fp32.  A row whose step rounds to zero gets delta = 0, q = 0.
+ */
+int quasar_quantize_weights(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw,
+                            int8_t *wq_packed, uint16_t *scales_bf16, void *hip_stream);
+
+/* Inverse of the packing permutation: packed -> q[N, K] row-major int8 (device). */
+int quasar_unpack_weights(const int8_t *wq_packed, int64_t N, int64_t K,
+                          int8_t *q_rowmajor, void *hip_stream);
+
+/*
+ * Quantised linear layer of the verifier (Sec. 3.2 Eq. 8 integer-code matmul,
+ * Sec. 3.3 Eq. 10 dequantisation), activations kept in bf16:
+ *     y[m, n] = bf16( ( sum_k x[m, k] * q[n, k] ) * delta_n ),  fp32 accumulation.
+ *   x  device [M, K] bf16, row stride ldx        y  device out [M, N] bf16, row stride ldy
+ *   wq_packed / scales_bf16 as produced by quasar_quantize_weights
+ *   workspace may be NULL (unused today).
+ * Weight bytes are read from HBM exactly once (the 1-byte-per-parameter term of
+ * Eq. 12).
+ */
+int quasar_w8_linear(const uint16_t *x, int64_t M, int64_t K, int64_t ldx,
+                     const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t N,
+                     uint16_t *y, int64_t ldy,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Vocabulary projection fused with the acceptance decision (Sec. 3.1 Eq. 2 in
+ * its temperature-0, deterministic-drafter case; Sec. 3.3 "Lossless Rejection
+ * Sampling"): logits[m, v] as in quasar_w8_linear but compared in fp32 without
+ * rounding to bf16 and never written to memory;
+ *     out_argmax[m]     = smallest v attaining max_v logits[m, v]        (M values)
+ *     out_accept_len[0] = number of leading i < n_draft with out_argmax[i] == draft_ids[i]
+ * so the token to emit after the accepted prefix is out_argmax[out_accept_len].
+ *   hidden device [M, K] bf16 (row stride ldh); draft_ids device [n_draft] int32,
+ *   0 <= n_draft <= M (may be NULL when n_draft == 0); ids outside [0, V) never match.
+ *   workspace: device, >= quasar_workspace_bytes(M, V, K) bytes.
+ */
+int quasar_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh,
+                         const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t V,
+                         const int32_t *draft_ids, int64_t n_draft,
+                         int32_t *out_argmax, int32_t *out_accept_len,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Full-precision comparison point (Sec. 3.4 Eq. 11: two bytes per parameter):
+ * the same kernels streaming bf16 weights.  quasar_pack_bf16_weights converts
+ * (fp32 -> bf16 round-to-nearest-even, or copies bf16) into the tile order.
+ */
+int quasar_pack_bf16_weights(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw,
+                             uint16_t *w_packed, void *hip_stream);
+int quasar_bf16_linear(const uint16_t *x, int64_t M, int64_t K, int64_t ldx,
+                       const uint16_t *w_packed, int64_t N,
+                       uint16_t *y, int64_t ldy,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+int quasar_bf16_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh,
+                              const uint16_t *w_packed, int64_t V,
+                              const int32_t *draft_ids, int64_t n_draft,
+                              int32_t *out_argmax, int32_t *out_accept_len,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Measurement helpers (the bandwidth term of Eq. 11-12 measured directly).
+ * quasar_read_stream reads `bytes` (multiple of 16) from `src` with the same
+ * load pattern as the linear kernels and writes one checksum word per workgroup
+ * into sink (device, >= 8192 bytes).  quasar_copy_stream copies `bytes`
+ * (multiple of 16) from src to dst; it is the plain copy kernel of known size
+ * used to calibrate hardware byte counters.
+ */
+int quasar_read_stream(const void *src, size_t bytes, void *sink, void *hip_stream);
+int quasar_copy_stream(void *dst, const void *src, size_t bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUASAR_H_ */

@@ -1,0 +1,246 @@
+"""Thin ctypes binding over libquasar.so: argument marshalling only.
+
+Every function takes torch CUDA tensors (used purely as device memory), passes
+their device pointers and the current torch stream to the C entry point of the
+same name, and raises on a non-zero status.  There is no CPU path: importing
+this module without the built library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # imported first so that the library binds to the HIP runtime torch loaded
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libquasar.so")
+
+F32, BF16 = 0, 1
+PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
+
+# every symbol declared in include/quasar.h
+EXPORTS = (
+    "quasar_status_string", "quasar_version", "quasar_set_path", "quasar_get_path",
+    "quasar_packed_bytes", "quasar_packed_bytes_bf16", "quasar_workspace_bytes",
+    "quasar_quantize_weights", "quasar_unpack_weights", "quasar_w8_linear", "quasar_lmhead_verify",
+    "quasar_pack_bf16_weights", "quasar_bf16_linear", "quasar_bf16_lmhead_verify",
+    "quasar_read_stream", "quasar_copy_stream",
+)
+
+
+class QuasarError(RuntimeError):
+    def __init__(self, fn: str, status: int, text: str):
+        super().__init__(f"{fn} failed: status {status} ({text})")
+        self.status = status
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2603_01399_amd.build` "
+            "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, sz, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    lib.quasar_status_string.argtypes = [ci]
+    lib.quasar_status_string.restype = ctypes.c_char_p
+    lib.quasar_version.argtypes = []
+    lib.quasar_version.restype = ci
+    lib.quasar_set_path.argtypes = [ci]
+    lib.quasar_get_path.argtypes = []
+    lib.quasar_set_tuning.argtypes = [ci, ci]
+    for name in ("quasar_packed_bytes", "quasar_packed_bytes_bf16"):
+        getattr(lib, name).argtypes = [i64, i64]
+        getattr(lib, name).restype = sz
+    lib.quasar_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.quasar_workspace_bytes.restype = sz
+    lib.quasar_quantize_weights.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp]
+    lib.quasar_unpack_weights.argtypes = [vp, i64, i64, vp, vp]
+    lib.quasar_w8_linear.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, vp, sz, vp]
+    lib.quasar_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, vp, vp, vp, sz, vp]
+    lib.quasar_pack_bf16_weights.argtypes = [vp, ci, i64, i64, i64, vp, vp]
+    lib.quasar_bf16_linear.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, sz, vp]
+    lib.quasar_bf16_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, sz, vp]
+    lib.quasar_read_stream.argtypes = [vp, sz, vp, vp]
+    lib.quasar_copy_stream.argtypes = [vp, vp, sz, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def lib() -> ctypes.CDLL:
+    return _lib
+
+
+def _check(fn: str, status: int) -> None:
+    if status != 0:
+        raise QuasarError(fn, status, _lib.quasar_status_string(status).decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, name, dtype=None):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return t
+
+
+def status_string(status: int) -> str:
+    return _lib.quasar_status_string(status).decode()
+
+
+def version() -> int:
+    return _lib.quasar_version()
+
+
+def set_path(path: int) -> None:
+    _check("quasar_set_path", _lib.quasar_set_path(path))
+
+
+def get_path() -> int:
+    return _lib.quasar_get_path()
+
+
+def set_tuning(waves: int, wgs_per_cu: int) -> None:
+    _check("quasar_set_tuning", _lib.quasar_set_tuning(waves, wgs_per_cu))
+
+
+def packed_bytes(N: int, K: int) -> int:
+    return _lib.quasar_packed_bytes(N, K)
+
+
+def packed_bytes_bf16(N: int, K: int) -> int:
+    return _lib.quasar_packed_bytes_bf16(N, K)
+
+
+def workspace_bytes(M: int, N: int, K: int) -> int:
+    return _lib.quasar_workspace_bytes(M, N, K)
+
+
+def quantize_weights(w: torch.Tensor, wq_packed: torch.Tensor = None, scales: torch.Tensor = None):
+    """w [N, K] fp32 or bf16 (last dim contiguous) -> (packed int8 [N*K], scales bf16 [N])."""
+    _dev(w, "w")
+    if w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be [N, K] with a contiguous last dimension")
+    dt = {torch.float32: F32, torch.bfloat16: BF16}.get(w.dtype)
+    if dt is None:
+        raise TypeError("w must be float32 or bfloat16")
+    N, K = w.shape
+    if wq_packed is None:
+        wq_packed = torch.empty(max(packed_bytes(N, K), 1), dtype=torch.int8, device=w.device)
+    if scales is None:
+        scales = torch.empty(N, dtype=torch.bfloat16, device=w.device)
+    _check("quasar_quantize_weights",
+           _lib.quasar_quantize_weights(_ptr(w), dt, N, K, w.stride(0), _ptr(wq_packed), _ptr(scales), _stream()))
+    return wq_packed, scales
+
+
+def unpack_weights(wq_packed: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    _dev(wq_packed, "wq_packed", torch.int8)
+    q = torch.empty((N, K), dtype=torch.int8, device=wq_packed.device)
+    _check("quasar_unpack_weights", _lib.quasar_unpack_weights(_ptr(wq_packed), N, K, _ptr(q), _stream()))
+    return q
+
+
+def w8_linear(x: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Tensor, N: int,
+              y: torch.Tensor = None, workspace: torch.Tensor = None) -> torch.Tensor:
+    _dev(x, "x", torch.bfloat16)
+    _dev(wq_packed, "wq_packed", torch.int8)
+    _dev(scales, "scales", torch.bfloat16)
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check("quasar_w8_linear",
+           _lib.quasar_w8_linear(_ptr(x), M, K, x.stride(0), _ptr(wq_packed), _ptr(scales), N,
+                                 _ptr(y), y.stride(0), _ptr(workspace), ws_bytes, _stream()))
+    return y
+
+
+def make_workspace(M: int, N: int, K: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(workspace_bytes(M, N, K), 16), dtype=torch.uint8, device=device)
+
+
+def lmhead_verify(hidden: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Tensor, V: int,
+                  draft_ids: torch.Tensor, workspace: torch.Tensor,
+                  out_argmax: torch.Tensor = None, out_accept: torch.Tensor = None):
+    _dev(hidden, "hidden", torch.bfloat16)
+    _dev(wq_packed, "wq_packed", torch.int8)
+    _dev(scales, "scales", torch.bfloat16)
+    M, K = hidden.shape
+    n_draft = 0 if draft_ids is None else draft_ids.numel()
+    if n_draft:
+        _dev(draft_ids, "draft_ids", torch.int32)
+    if out_argmax is None:
+        out_argmax = torch.empty(M, dtype=torch.int32, device=hidden.device)
+    if out_accept is None:
+        out_accept = torch.empty(1, dtype=torch.int32, device=hidden.device)
+    _check("quasar_lmhead_verify",
+           _lib.quasar_lmhead_verify(_ptr(hidden), M, K, hidden.stride(0), _ptr(wq_packed), _ptr(scales), V,
+                                     _ptr(draft_ids) if n_draft else None, n_draft, _ptr(out_argmax),
+                                     _ptr(out_accept), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream()))
+    return out_argmax, out_accept
+
+
+def pack_bf16_weights(w: torch.Tensor, w_packed: torch.Tensor = None) -> torch.Tensor:
+    _dev(w, "w")
+    if w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be [N, K] with a contiguous last dimension")
+    dt = {torch.float32: F32, torch.bfloat16: BF16}.get(w.dtype)
+    if dt is None:
+        raise TypeError("w must be float32 or bfloat16")
+    N, K = w.shape
+    if w_packed is None:
+        w_packed = torch.empty(N * K, dtype=torch.bfloat16, device=w.device)
+    _check("quasar_pack_bf16_weights",
+           _lib.quasar_pack_bf16_weights(_ptr(w), dt, N, K, w.stride(0), _ptr(w_packed), _stream()))
+    return w_packed
+
+
+def bf16_linear(x: torch.Tensor, w_packed: torch.Tensor, N: int, y: torch.Tensor = None) -> torch.Tensor:
+    _dev(x, "x", torch.bfloat16)
+    _dev(w_packed, "w_packed", torch.bfloat16)
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _check("quasar_bf16_linear",
+           _lib.quasar_bf16_linear(_ptr(x), M, K, x.stride(0), _ptr(w_packed), N, _ptr(y), y.stride(0),
+                                   None, 0, _stream()))
+    return y
+
+
+def bf16_lmhead_verify(hidden: torch.Tensor, w_packed: torch.Tensor, V: int, draft_ids: torch.Tensor,
+                       workspace: torch.Tensor, out_argmax: torch.Tensor = None, out_accept: torch.Tensor = None):
+    _dev(hidden, "hidden", torch.bfloat16)
+    _dev(w_packed, "w_packed", torch.bfloat16)
+    M, K = hidden.shape
+    n_draft = 0 if draft_ids is None else draft_ids.numel()
+    if out_argmax is None:
+        out_argmax = torch.empty(M, dtype=torch.int32, device=hidden.device)
+    if out_accept is None:
+        out_accept = torch.empty(1, dtype=torch.int32, device=hidden.device)
+    _check("quasar_bf16_lmhead_verify",
+           _lib.quasar_bf16_lmhead_verify(_ptr(hidden), M, K, hidden.stride(0), _ptr(w_packed), V,
+                                          _ptr(draft_ids) if n_draft else None, n_draft, _ptr(out_argmax),
+                                          _ptr(out_accept), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream()))
+    return out_argmax, out_accept
+
+
+def read_stream(src: torch.Tensor, sink: torch.Tensor, nbytes: int = None) -> None:
+    nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
+    _check("quasar_read_stream", _lib.quasar_read_stream(_ptr(src), nbytes, _ptr(sink), _stream()))
+
+
+def copy_stream(dst: torch.Tensor, src: torch.Tensor, nbytes: int = None) -> None:
+    nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
+    _check("quasar_copy_stream", _lib.quasar_copy_stream(_ptr(dst), _ptr(src), nbytes, _stream()))

@@ -1,0 +1,520 @@
+// Skinny-M weight-streaming contraction kernels (gfx950).
+//
+// One workgroup owns a contiguous range of 16-row weight tiles and walks the K
+// dimension of every tile with all of its waves: wave w takes the w-th slice of
+// the tile's 1 KB "steps", keeps a ring of D 128-bit loads in flight (the ring
+// runs ahead across tile and chunk boundaries because weight addresses do not
+// depend on the activations), and the per-wave partial tiles are summed through
+// LDS in a fixed order.  Activations for the current K chunk sit in LDS in
+// operand order.  The packed weight layout makes the whole workgroup stream
+// one contiguous address range.
+#pragma once
+
+#include "quasar_device.hpp"
+
+namespace quasar {
+
+struct GemmParams {
+    const uint16_t *x;       // [M, K] bf16, row stride ldx
+    long long ldx;
+    const u32x4 *w;          // packed weights, 64 x 16 B per step, steps of a tile contiguous
+    const uint16_t *scales;  // [N] bf16 step sizes (nullptr for bf16 weights)
+    uint16_t *y;             // [M, N] bf16, row stride ldy          (linear epilogue)
+    long long ldy;
+    unsigned long long *partial;  // [gridDim.x][MP] packed (logit, index) keys  (argmax epilogue)
+    int M, N, K;
+    int T;          // number of 16-row tiles
+    int S;          // steps per tile (K/64 for int8, K/32 for bf16 weights)
+    int SC;         // steps per K chunk (activations of one chunk fit in LDS)
+    int C;          // number of K chunks
+    int xs_bytes;   // LDS bytes reserved for the activation chunk
+    int sc_bytes;   // LDS bytes reserved for the workgroup's row scales
+};
+
+enum { EPI_LINEAR = 0, EPI_ARGMAX = 1 };
+
+// ------------------------------------------------------------------------------------
+// Per-wave walk over the workgroup's (chunk, tile, step) sequence with a ring of D loads.
+//
+// Sequence of one wave: for every K chunk c, for every tile of the workgroup, the wave's
+// slice of the chunk's steps (at least one slot per tile so that every wave reaches every
+// tile-end barrier), padded per chunk to a multiple of D.  Slot j of the sequence is
+// loaded into ring[j % D] exactly D slots before it is consumed; slots that carry no
+// step (padding, empty slices) load a fixed hot address and contribute zeros.  Every
+// iteration issues exactly one load per consumed slot, unconditionally, so the compiler
+// can count outstanding loads and never drains the ring.
+// ------------------------------------------------------------------------------------
+// Ties the address of a ring refill to the registers just consumed: the refill cannot be
+// moved above the last read of the slot's old contents, so old and new value share the
+// same registers and the ring is never copied (which would drain it) at a loop back-edge.
+typedef const __attribute__((address_space(1))) u32x4 *global_u32x4_ptr;
+
+__device__ __forceinline__ u32x4 load_after_use(const u32x4 *addr, const u32x4 &used) {
+    unsigned long long a = reinterpret_cast<unsigned long long>(addr);
+    asm volatile("" : "+v"(a) : "v"(used.x), "v"(used.y), "v"(used.z), "v"(used.w));
+    return __builtin_nontemporal_load(reinterpret_cast<global_u32x4_ptr>(a));
+}
+
+template <int NW, int D>
+struct WaveWalk {
+    const GemmParams &p;
+    int w, lane, t0, ntiles;
+
+    struct Front { int c, idx, tl, si, s_lo, spw, nsl, items, padded; };
+
+    __device__ __forceinline__ void slice(int c, Front &f) const {
+        const int scc = min(p.SC, p.S - c * p.SC);
+        f.s_lo = (scc * w) / NW;
+        f.spw = (scc * (w + 1)) / NW - f.s_lo;
+        f.nsl = max(f.spw, 1);
+        f.items = ntiles * f.nsl;
+        f.padded = ((f.items + D - 1) / D) * D;
+    }
+    __device__ __forceinline__ void begin(Front &f) const {
+        f.c = 0; f.idx = 0; f.tl = 0; f.si = 0;
+        slice(0, f);
+    }
+    __device__ __forceinline__ void advance(Front &f) const {
+        ++f.idx;
+        ++f.si;
+        if (f.si >= f.nsl) { f.si = 0; ++f.tl; }
+        if (f.idx == f.padded) {
+            ++f.c; f.idx = 0; f.tl = 0; f.si = 0;
+            if (f.c < p.C) slice(f.c, f); else { f.items = 0; f.padded = D; f.spw = 0; f.nsl = 1; }
+        }
+    }
+    __device__ __forceinline__ const u32x4 *addr(const Front &f) const {
+        const bool real = f.c < p.C && f.idx < f.items && f.si < f.spw;
+        const long long step = (long long)(t0 + f.tl) * p.S + (long long)f.c * p.SC + f.s_lo + f.si;
+        return p.w + (real ? step * 64 : 0ll) + lane;
+    }
+};
+
+// ------------------------------------------------------------------------------------
+// MFMA variant.  A operand = 16 weight rows x 32 k (bf16, converted in registers from the
+// int8 codes), B operand = 32 k x 16 tokens from LDS, D = 16 rows x 16 tokens fp32.
+// Lane l = 16*g + i holds weight row i, k-group g (A) / token i, k-group g (B) and
+// accumulates rows 4g..4g+3 of token i (D).
+// LDS: [activation chunk][scales of the workgroup's tiles][2 x NW staging tiles][tile sums]
+// ------------------------------------------------------------------------------------
+template <int MP, bool W16, int EPI, int NW, int D>
+__global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int NB = (MP == 32) ? 2 : 1;   // 16-token blocks
+    constexpr int PPS = W16 ? 4 : 8;         // 16-byte activation pieces (8 k) per step
+    constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
+    constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
+    constexpr int XB = 8;                    // activation pieces per thread per batch
+    constexpr int nthreads = NW * 64;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, mcol = lane & 15;
+
+    const int G = gridDim.x, b = blockIdx.x;
+    const int t0 = (int)(((long long)p.T * b) / G);
+    const int t1 = (int)(((long long)p.T * (b + 1)) / G);
+    const int ntiles = t1 - t0;
+
+    u32x4 *xs = reinterpret_cast<u32x4 *>(lds);                                   // [SC*PPS][MP]
+    uint16_t *sc_lds = reinterpret_cast<uint16_t *>(lds + p.xs_bytes);            // [tpw*16]
+    f32x4 *stage = reinterpret_cast<f32x4 *>(lds + p.xs_bytes + p.sc_bytes);      // [2][NW][NB][64]
+    f32x4 *accs = stage + 2 * NW * NB * 64;                                       // [ntiles][NB][64] (C > 1)
+
+    auto x_piece_load = [&](int c, int idx) -> u32x4 {
+        const int scc = min(p.SC, p.S - c * p.SC);
+        const int npieces = scc * PPS * MP;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (idx < npieces) {
+            const int m = idx & (MP - 1), p8 = idx >> LMP;
+            if (m < p.M) {
+                const long long k = (long long)c * p.SC * KSTEP + 8ll * p8;
+                v = *reinterpret_cast<const u32x4 *>(p.x + m * p.ldx + k);
+            }
+        }
+        return v;
+    };
+    auto x_stage = [&](int c, int first_batch) {
+        const int scc = min(p.SC, p.S - c * p.SC);
+        const int npieces = scc * PPS * MP;
+        for (int base = first_batch * nthreads * XB; base < npieces; base += nthreads * XB) {
+            u32x4 v[XB];
+#pragma unroll
+            for (int i = 0; i < XB; ++i) v[i] = x_piece_load(c, base + i * nthreads + tid);
+#pragma unroll
+            for (int i = 0; i < XB; ++i) {
+                const int idx = base + i * nthreads + tid;
+                if (idx < npieces) xs[idx] = v[i];
+            }
+        }
+    };
+
+    WaveWalk<NW, D> walk{p, w, lane, t0, ntiles};
+    typename WaveWalk<NW, D>::Front ld;
+    walk.begin(ld);
+
+    // requests in the order they are needed back: first activation batch, scales, weight ring
+    u32x4 xfirst[XB];
+#pragma unroll
+    for (int i = 0; i < XB; ++i) xfirst[i] = x_piece_load(0, i * nthreads + tid);
+    unsigned int sc_first = 0;
+    if constexpr (!W16) {
+        if (2 * tid < ntiles * kTileRows)
+            sc_first = *reinterpret_cast<const unsigned int *>(p.scales + (long long)t0 * kTileRows + 2 * tid);
+    }
+    u32x4 ring[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        ring[d] = __builtin_nontemporal_load(walk.addr(ld));
+        walk.advance(ld);
+    }
+    {
+        const int npieces = min(p.SC, p.S) * PPS * MP;
+#pragma unroll
+        for (int i = 0; i < XB; ++i) {
+            const int idx = i * nthreads + tid;
+            if (idx < npieces) xs[idx] = xfirst[i];
+        }
+        if constexpr (!W16) {
+            if (2 * tid < ntiles * kTileRows) reinterpret_cast<unsigned int *>(sc_lds)[tid] = sc_first;
+            for (int i = 2 * (tid + nthreads); i < ntiles * kTileRows; i += 2 * nthreads)
+                reinterpret_cast<unsigned int *>(sc_lds)[i >> 1] =
+                    *reinterpret_cast<const unsigned int *>(p.scales + (long long)t0 * kTileRows + i);
+        }
+        x_stage(0, 1);
+        lds_barrier();
+    }
+
+    f32x4 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float bestv[NB];
+    unsigned int besti[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) { bestv[nb] = -__builtin_inff(); besti[nb] = 0x7FFFFFFFu; }
+    int parity = 0;
+    const int xm = (MP == 8) ? (mcol & 7) : mcol;   // token slot read by this lane
+
+    for (int c = 0; c < p.C; ++c) {
+        if (c > 0) {
+            // every wave has passed the previous chunk's last tile barrier: the chunk's
+            // activations are no longer read
+            x_stage(c, 0);
+            // full drain: the staging loads are conditional, and without a known-empty load
+            // queue here the compiler would fall back to draining the ring on every round
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            lds_barrier();
+        }
+        typename WaveWalk<NW, D>::Front cs;
+        walk.slice(c, cs);
+        int tl = 0, si = 0;
+        const int rounds = cs.padded / D;
+        for (int r = 0; r < rounds; ++r) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const int idx = r * D + d;
+                const bool in_range = idx < cs.items;
+                const bool valid = in_range && si < cs.spw;
+                u32x4 wv = ring[d];
+                if (!valid) wv = u32x4{0u, 0u, 0u, 0u};
+                const int step_in_chunk = valid ? cs.s_lo + si : 0;
+                const int piece0 = step_in_chunk * PPS;
+                if constexpr (!W16) {
+                    const bf16x8 a0 = codes_to_bf16x8(wv.x, wv.y);
+                    const bf16x8 a1 = codes_to_bf16x8(wv.z, wv.w);
+                    ring[d] = load_after_use(walk.addr(ld), wv);
+                    walk.advance(ld);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const u32x4 b0 = xs[(piece0 + 2 * g) * MP + xm + 16 * nb];
+                        const u32x4 b1 = xs[(piece0 + 2 * g + 1) * MP + xm + 16 * nb];
+                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0),
+                                                                          acc[nb], 0, 0, 0);
+                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1),
+                                                                          acc[nb], 0, 0, 0);
+                    }
+                } else {
+                    const bf16x8 a0 = __builtin_bit_cast(bf16x8, wv);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const u32x4 b0 = xs[(piece0 + g) * MP + xm + 16 * nb];
+                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0),
+                                                                          acc[nb], 0, 0, 0);
+                    }
+                    ring[d] = load_after_use(walk.addr(ld), wv);
+                    walk.advance(ld);
+                }
+                if (in_range && si == cs.nsl - 1) {
+                    // ---- tile end: cross-wave sum through LDS, fixed order
+                    f32x4 *st = stage + (parity * NW) * NB * 64;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        st[(w * NB + nb) * 64 + lane] = acc[nb];
+                        acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                    lds_barrier();
+                    if (w == (tl % NW)) {
+                        f32x4 rsum[NB];
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) {
+                            rsum[nb] = st[nb * 64 + lane];
+#pragma unroll
+                            for (int ww = 1; ww < NW; ++ww) rsum[nb] += st[(ww * NB + nb) * 64 + lane];
+                            if (p.C > 1) {
+                                f32x4 *a = accs + (tl * NB + nb) * 64 + lane;
+                                if (c > 0) rsum[nb] += *a;
+                                if (c < p.C - 1) *a = rsum[nb];
+                            }
+                        }
+                        if (c == p.C - 1) {
+                            const int n0 = (t0 + tl) * kTileRows + 4 * g;
+                            float s4[4] = {1.f, 1.f, 1.f, 1.f};
+                            if constexpr (!W16) {
+                                const u32x2 sb = *reinterpret_cast<const u32x2 *>(sc_lds + tl * kTileRows + 4 * g);
+                                s4[0] = bf16_bits_to_float(sb.x & 0xFFFFu);
+                                s4[1] = bf16_bits_to_float(sb.x >> 16);
+                                s4[2] = bf16_bits_to_float(sb.y & 0xFFFFu);
+                                s4[3] = bf16_bits_to_float(sb.y >> 16);
+                            }
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb) {
+                                const int m = mcol + 16 * nb;
+                                const float v0 = rsum[nb].x * s4[0], v1 = rsum[nb].y * s4[1];
+                                const float v2 = rsum[nb].z * s4[2], v3 = rsum[nb].w * s4[3];
+                                if constexpr (EPI == EPI_LINEAR) {
+                                    if (m < p.M) {
+                                        u32x2 o;
+                                        o.x = float_to_bf16_bits(v0) | (float_to_bf16_bits(v1) << 16);
+                                        o.y = float_to_bf16_bits(v2) | (float_to_bf16_bits(v3) << 16);
+                                        *reinterpret_cast<u32x2 *>(p.y + m * p.ldy + n0) = o;
+                                    }
+                                } else {
+                                    // strictly greater keeps the lowest index inside a lane
+                                    if (v0 > bestv[nb]) { bestv[nb] = v0; besti[nb] = n0; }
+                                    if (v1 > bestv[nb]) { bestv[nb] = v1; besti[nb] = n0 + 1; }
+                                    if (v2 > bestv[nb]) { bestv[nb] = v2; besti[nb] = n0 + 2; }
+                                    if (v3 > bestv[nb]) { bestv[nb] = v3; besti[nb] = n0 + 3; }
+                                }
+                            }
+                        }
+                    }
+                    parity ^= 1;
+                }
+                if (in_range) {
+                    ++si;
+                    if (si >= cs.nsl) { si = 0; ++tl; }
+                }
+            }
+        }
+    }
+
+    if constexpr (EPI == EPI_ARGMAX) {
+        // per wave: combine the four k-groups' row subsets, then combine waves, then publish
+        unsigned long long *red = reinterpret_cast<unsigned long long *>(stage);   // [NW][MP]
+        lds_barrier();   // all tile-end reads of the staging area are done
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            unsigned long long key = argmax_key(bestv[nb], besti[nb]);
+            unsigned long long o = shfl_xor_u64(key, 16);
+            key = o > key ? o : key;
+            o = shfl_xor_u64(key, 32);
+            key = o > key ? o : key;
+            if (g == 0 && (MP != 8 || mcol < 8)) red[w * MP + mcol + 16 * nb] = key;
+        }
+        lds_barrier();
+        if (tid < MP) {
+            unsigned long long key = red[tid];
+            for (int ww = 1; ww < NW; ++ww) {
+                const unsigned long long o = red[ww * MP + tid];
+                key = o > key ? o : key;
+            }
+            p.partial[(long long)b * MP + tid] = key;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// VALU variant for M <= 4: fp32 FMA dot products, no matrix cores.  Lane l = 16*g + i holds
+// 16 consecutive k of weight row i per step; activations sit in LDS as fp32 [M][Kchunk]
+// (all lanes of a k-group read the same address: a broadcast).  The k-groups of a lane
+// row are combined with cross-lane shuffles, the waves through LDS.
+// ------------------------------------------------------------------------------------
+template <int MV, int NW, int D>
+__global__ __launch_bounds__(NW * 64) void stream_valu_kernel(const GemmParams p) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr int nthreads = NW * 64;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, i16 = lane & 15;
+
+    const int G = gridDim.x, b = blockIdx.x;
+    const int t0 = (int)(((long long)p.T * b) / G);
+    const int t1 = (int)(((long long)p.T * (b + 1)) / G);
+    const int ntiles = t1 - t0;
+    const int kc_max = p.SC * kStepK8;
+
+    float *xs = reinterpret_cast<float *>(lds);                                   // [MV][kc_max]
+    uint16_t *sc_lds = reinterpret_cast<uint16_t *>(lds + p.xs_bytes);            // [tpw*16]
+    float *stage = reinterpret_cast<float *>(lds + p.xs_bytes + p.sc_bytes);      // [2][NW][MV][16]
+    float *accs = stage + 2 * NW * MV * 16;                                       // [ntiles][MV][16]
+
+    auto x_stage = [&](int c) {
+        const int scc = min(p.SC, p.S - c * p.SC);
+        const int kc8 = scc * (kStepK8 / 8);         // 8 bf16 per piece
+        const int npieces = kc8 * MV;
+        for (int idx = tid; idx < npieces; idx += nthreads) {
+            const int m = idx / kc8, p8 = idx - m * kc8;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (m < p.M)
+                v = *reinterpret_cast<const u32x4 *>(p.x + m * p.ldx + (long long)c * p.SC * kStepK8 + 8 * p8);
+            f32x4 lo, hi;
+            lo.x = __uint_as_float(v.x << 16); lo.y = __uint_as_float(v.x & 0xFFFF0000u);
+            lo.z = __uint_as_float(v.y << 16); lo.w = __uint_as_float(v.y & 0xFFFF0000u);
+            hi.x = __uint_as_float(v.z << 16); hi.y = __uint_as_float(v.z & 0xFFFF0000u);
+            hi.z = __uint_as_float(v.w << 16); hi.w = __uint_as_float(v.w & 0xFFFF0000u);
+            f32x4 *dst = reinterpret_cast<f32x4 *>(xs + m * kc_max + 8 * p8);
+            dst[0] = lo;
+            dst[1] = hi;
+        }
+    };
+
+    WaveWalk<NW, D> walk{p, w, lane, t0, ntiles};
+    typename WaveWalk<NW, D>::Front ld;
+    walk.begin(ld);
+
+    for (int i = 2 * tid; i < ntiles * kTileRows; i += 2 * nthreads)
+        reinterpret_cast<unsigned int *>(sc_lds)[i >> 1] =
+            *reinterpret_cast<const unsigned int *>(p.scales + (long long)t0 * kTileRows + i);
+    x_stage(0);
+    u32x4 ring[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        ring[d] = __builtin_nontemporal_load(walk.addr(ld));
+        walk.advance(ld);
+    }
+    lds_barrier();
+
+    float acc[MV];
+#pragma unroll
+    for (int m = 0; m < MV; ++m) acc[m] = 0.f;
+    int parity = 0;
+
+    for (int c = 0; c < p.C; ++c) {
+        if (c > 0) {
+            x_stage(c);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), as in the MFMA kernel
+            lds_barrier();
+        }
+        typename WaveWalk<NW, D>::Front cs;
+        walk.slice(c, cs);
+        int tl = 0, si = 0;
+        const int rounds = cs.padded / D;
+        for (int r = 0; r < rounds; ++r) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const int idx = r * D + d;
+                const bool in_range = idx < cs.items;
+                const bool valid = in_range && si < cs.spw;
+                u32x4 wv = ring[d];
+                if (!valid) wv = u32x4{0u, 0u, 0u, 0u};
+                float wf[16];
+                const unsigned int wd[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    wf[4 * q + 0] = (float)(signed char)(wd[q] & 0xff);
+                    wf[4 * q + 1] = (float)(signed char)((wd[q] >> 8) & 0xff);
+                    wf[4 * q + 2] = (float)(signed char)((wd[q] >> 16) & 0xff);
+                    wf[4 * q + 3] = (float)(signed char)(wd[q] >> 24);
+                }
+                ring[d] = load_after_use(walk.addr(ld), wv);
+                walk.advance(ld);
+                const int k0 = (valid ? cs.s_lo + si : 0) * kStepK8 + 16 * g;
+#pragma unroll
+                for (int m = 0; m < MV; ++m) {
+                    const f32x4 *xp = reinterpret_cast<const f32x4 *>(xs + m * kc_max + k0);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x4 xv = xp[q];
+                        acc[m] = __builtin_fmaf(wf[4 * q + 0], xv.x, acc[m]);
+                        acc[m] = __builtin_fmaf(wf[4 * q + 1], xv.y, acc[m]);
+                        acc[m] = __builtin_fmaf(wf[4 * q + 2], xv.z, acc[m]);
+                        acc[m] = __builtin_fmaf(wf[4 * q + 3], xv.w, acc[m]);
+                    }
+                }
+                if (in_range && si == cs.nsl - 1) {
+                    float *st = stage + parity * NW * MV * 16;
+#pragma unroll
+                    for (int m = 0; m < MV; ++m) {
+                        float v = acc[m];
+                        v += __shfl_xor(v, 16, 64);
+                        v += __shfl_xor(v, 32, 64);
+                        if (g == 0) st[(w * MV + m) * 16 + i16] = v;
+                        acc[m] = 0.f;
+                    }
+                    lds_barrier();
+                    if (w == (tl % NW) && lane < MV * 16) {
+                        const int m = lane >> 4;
+                        float rsum = st[m * 16 + i16];
+#pragma unroll
+                        for (int ww = 1; ww < NW; ++ww) rsum += st[(ww * MV + m) * 16 + i16];
+                        if (p.C > 1) {
+                            float *a = accs + (tl * MV + m) * 16 + i16;
+                            if (c > 0) rsum += *a;
+                            if (c < p.C - 1) *a = rsum;
+                        }
+                        if (c == p.C - 1 && m < p.M) {
+                            const int n = (t0 + tl) * kTileRows + i16;
+                            const float v = rsum * bf16_bits_to_float(sc_lds[tl * kTileRows + i16]);
+                            p.y[m * p.ldy + n] = (uint16_t)float_to_bf16_bits(v);
+                        }
+                    }
+                    parity ^= 1;
+                }
+                if (in_range) {
+                    ++si;
+                    if (si >= cs.nsl) { si = 0; ++tl; }
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Second stage of the fused verify: combine the per-workgroup keys, then count leading
+// draft matches.  One workgroup of 1024 threads, 32 threads per token position.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void verify_finalize_kernel(const unsigned long long *partial, int nparts,
+                                                               int MP, int M, int V, const int32_t *draft,
+                                                               int n_draft, int32_t *out_argmax,
+                                                               int32_t *out_accept) {
+    __shared__ int32_t am[32];
+    const int tid = threadIdx.x;
+    const int m = tid >> 5, sub = tid & 31;
+    unsigned long long key = 0ull;
+    if (m < M)
+        for (int i = sub; i < nparts; i += 32) {
+            const unsigned long long o = partial[(long long)i * MP + m];
+            key = o > key ? o : key;
+        }
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) {
+        const unsigned long long o = shfl_xor_u64(key, off);
+        key = o > key ? o : key;
+    }
+    if (m < M && sub == 0) {
+        unsigned int idx = argmax_key_index(key);
+        if (idx >= (unsigned int)V) idx = 0;   // only reachable with non-finite logits
+        am[m] = (int32_t)idx;
+        out_argmax[m] = (int32_t)idx;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int n = 0;
+        while (n < n_draft && am[n] == draft[n]) ++n;
+        out_accept[0] = n;
+    }
+}
+
+}  // namespace quasar

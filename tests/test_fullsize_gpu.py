@@ -1,0 +1,64 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration the benchmark times:
+every linear of one Qwen3-8B-shaped decoder layer at M in {1, 4, 8, 16}, and the fused
+vocabulary projection + greedy acceptance at V = 151936 (codes, scales, argmax and accepted
+length bit-exact; linear outputs within the stated tolerance, all elements compared)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import quasar_ref as ref
+from paper_2603_01399_amd import synth
+from gpu_util import bf16_to_dev, bf16_to_host, f32_to_dev, i32_to_dev
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def qb():
+    assert torch.cuda.is_available()
+    from paper_2603_01399_amd import binding
+    return binding
+
+
+def test_qwen3_8b_layer_linears_all_outputs(qb):
+    for li, (name, K, N) in enumerate(synth.QWEN3_8B_LAYER):
+        w = synth.normal_weights(N, K, seed=synth.seed_for(2, 0, li))
+        q_ref, s_ref = ref.quantize_weights(w)
+        wq, sc = qb.quantize_weights(f32_to_dev(w))
+        assert np.array_equal(qb.unpack_weights(wq, N, K).cpu().numpy(), q_ref), name
+        assert np.array_equal(bf16_to_host(sc), s_ref), name
+        for M in (1, 4, 8, 16):
+            xb = synth.activations_bf16(M, K, seed=synth.seed_for(2, 1, 10 * li + M))
+            y = qb.w8_linear(bf16_to_dev(xb), wq, sc, N)
+            torch.cuda.synchronize()
+            err = ref.rel_maxabs_err(ref.bf16_bits_to_f64(bf16_to_host(y)), ref.w8_linear(xb, q_ref, s_ref))
+            print(name, "M", M, "rel err", err, flush=True)
+            assert err <= TOL and err <= 4e-3
+
+
+@pytest.mark.parametrize("j", [3])
+def test_qwen3_lmhead_verify_full_vocab(qb, j):
+    M, K, V = 8, synth.QWEN3_8B_HIDDEN, synth.QWEN3_VOCAB
+    h = synth.activations_bf16(M, K, seed=synth.seed_for(3, 0, 0))
+    w = synth.normal_weights(V, K, seed=synth.seed_for(3, 0, 1))
+    t = synth.distinct_targets(M, V, seed=synth.seed_for(3, 0, 2))
+    synth.plant_targets(w, h, t)
+    print("quantising on both sides", flush=True)
+    q_ref, s_ref = ref.quantize_weights(w)
+    wq, sc = qb.quantize_weights(f32_to_dev(w))
+    assert np.array_equal(bf16_to_host(sc), s_ref)
+    assert np.array_equal(qb.unpack_weights(wq, V, K).cpu().numpy(), q_ref)
+    del w
+    ws = qb.make_workspace(M, V, K)
+    hd = bf16_to_dev(h)
+    print("oracle logits", flush=True)
+    base = ref.lmhead_verify(h, q_ref, s_ref, np.zeros(0, np.int32))
+    assert np.array_equal(base["argmax"], t)
+    assert np.all(base["top1"] - base["top2"] > TOL * base["maxabs"])
+    for jj in (0, j, 7):
+        d = synth.draft_with_matches(t, jj, V, M - 1)
+        am, acc = qb.lmhead_verify(hd, wq, sc, V, i32_to_dev(d), ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(am.cpu().numpy(), t)
+        assert int(acc.cpu()[0]) == jj == ref.accepted_length(base["argmax"], d)
