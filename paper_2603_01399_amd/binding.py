@@ -47,7 +47,7 @@ def _load() -> ctypes.CDLL:
     lib.quasar_version.restype = ci
     lib.quasar_set_path.argtypes = [ci]
     lib.quasar_get_path.argtypes = []
-    lib.quasar_set_tuning.argtypes = [ci, ci]
+    lib.quasar_set_tuning.argtypes = [ci, ci, ci]
     for name in ("quasar_packed_bytes", "quasar_packed_bytes_bf16"):
         getattr(lib, name).argtypes = [i64, i64]
         getattr(lib, name).restype = sz
@@ -109,8 +109,8 @@ def get_path() -> int:
     return _lib.quasar_get_path()
 
 
-def set_tuning(waves: int, wgs_per_cu: int) -> None:
-    _check("quasar_set_tuning", _lib.quasar_set_tuning(waves, wgs_per_cu))
+def set_tuning(waves: int, wgs_per_cu: int, depth: int = 8) -> None:
+    _check("quasar_set_tuning", _lib.quasar_set_tuning(waves, wgs_per_cu, depth))
 
 
 def packed_bytes(N: int, K: int) -> int:

@@ -26,7 +26,8 @@ constexpr int kMinLds = 82 * 1024;           // > half the LDS: at most one work
 constexpr int kMaxGrid = 4096;               // bound on workgroups (sizes the argmax partials)
 
 std::atomic<int> g_path{QUASAR_PATH_AUTO};
-std::atomic<int> g_tune_nw{8};
+std::atomic<int> g_tune_nw{16};
+std::atomic<int> g_tune_d{4};
 std::atomic<int> g_tune_wgs{1};
 
 struct EnvInit {
@@ -145,9 +146,12 @@ int launch_mfma(const GemmParams &base, int M, hipStream_t stream, int *grid_out
     p.xs_bytes = pl.xs_bytes;
     p.sc_bytes = pl.sc_bytes;
     if (grid_out) *grid_out = pl.grid;
+    const int DD = g_tune_d.load();
 #define QUASAR_LAUNCH(MPV)                                                                                   \
-    (NW == 16 ? launch(stream_mfma_kernel<MPV, W16, EPI, 16, 8>, pl.grid, 1024, pl.lds_bytes, stream, p)     \
-              : launch(stream_mfma_kernel<MPV, W16, EPI, 8, 16>, pl.grid, 512, pl.lds_bytes, stream, p))
+    (NW == 16 ? (DD == 8 ? launch(stream_mfma_kernel<MPV, W16, EPI, 16, 8>, pl.grid, 1024, pl.lds_bytes, stream, p) \
+                         : launch(stream_mfma_kernel<MPV, W16, EPI, 16, 4>, pl.grid, 1024, pl.lds_bytes, stream, p)) \
+              : (DD == 8 ? launch(stream_mfma_kernel<MPV, W16, EPI, 8, 8>, pl.grid, 512, pl.lds_bytes, stream, p)    \
+                         : launch(stream_mfma_kernel<MPV, W16, EPI, 8, 4>, pl.grid, 512, pl.lds_bytes, stream, p)))
     if (MP == 8) return QUASAR_LAUNCH(8);
     if (MP == 16) return QUASAR_LAUNCH(16);
     return QUASAR_LAUNCH(32);
@@ -163,9 +167,9 @@ int launch_valu(const GemmParams &base, int M, hipStream_t stream) {
     p.C = pl.C;
     p.xs_bytes = pl.xs_bytes;
     p.sc_bytes = pl.sc_bytes;
-    if (MV == 1) return launch(stream_valu_kernel<1, 8, 16>, pl.grid, 512, pl.lds_bytes, stream, p);
-    if (MV == 2) return launch(stream_valu_kernel<2, 8, 16>, pl.grid, 512, pl.lds_bytes, stream, p);
-    return launch(stream_valu_kernel<4, 8, 16>, pl.grid, 512, pl.lds_bytes, stream, p);
+    if (MV == 1) return launch(stream_valu_kernel<1, 8, 8>, pl.grid, 512, pl.lds_bytes, stream, p);
+    if (MV == 2) return launch(stream_valu_kernel<2, 8, 8>, pl.grid, 512, pl.lds_bytes, stream, p);
+    return launch(stream_valu_kernel<4, 8, 8>, pl.grid, 512, pl.lds_bytes, stream, p);
 }
 
 template <bool W16>
@@ -243,10 +247,12 @@ int quasar_get_path(void) { return g_path.load(); }
 
 /* development knob, not part of the documented contract: waves per workgroup (8 or 16) and
  * workgroups per compute unit (1..8) used by the streaming kernels */
-int quasar_set_tuning(int waves, int wgs_per_cu) {
-    if ((waves != 8 && waves != 16) || wgs_per_cu < 1 || wgs_per_cu > 8) return QUASAR_ERR_DTYPE;
+int quasar_set_tuning(int waves, int wgs_per_cu, int depth) {
+    if ((waves != 8 && waves != 16) || wgs_per_cu < 1 || wgs_per_cu > 8 || (depth != 4 && depth != 8))
+        return QUASAR_ERR_DTYPE;
     g_tune_nw = waves;
     g_tune_wgs = wgs_per_cu;
+    g_tune_d = depth;
     return QUASAR_OK;
 }
 

@@ -49,7 +49,10 @@ enum { EPI_LINEAR = 0, EPI_ARGMAX = 1 };
 // same registers and the ring is never copied (which would drain it) at a loop back-edge.
 typedef const __attribute__((address_space(1))) u32x4 *global_u32x4_ptr;
 
-__device__ __forceinline__ u32x4 load_after_use(const u32x4 *addr, const u32x4 &used) {
+// Ring refill.  The address is tied to the registers just consumed: the load cannot be moved
+// above the last read of the slot's old contents, so old and new value share registers and
+// the ring is never copied (which would drain it) at a loop back-edge.
+__device__ __forceinline__ u32x4 ring_refill(const u32x4 *addr, const u32x4 &used) {
     unsigned long long a = reinterpret_cast<unsigned long long>(addr);
     asm volatile("" : "+v"(a) : "v"(used.x), "v"(used.y), "v"(used.z), "v"(used.w));
     return __builtin_nontemporal_load(reinterpret_cast<global_u32x4_ptr>(a));
@@ -83,10 +86,15 @@ struct WaveWalk {
             if (f.c < p.C) slice(f.c, f); else { f.items = 0; f.padded = D; f.spw = 0; f.nsl = 1; }
         }
     }
+    __device__ __forceinline__ bool real(const Front &f) const {
+        return f.c < p.C && f.idx < f.items && f.si < f.spw;
+    }
+    // Slots without a step still issue a load (the in-order load counter needs one per slot):
+    // every lane reads the first 16 bytes of the activations, a single cache line that every
+    // compute unit already holds.
     __device__ __forceinline__ const u32x4 *addr(const Front &f) const {
-        const bool real = f.c < p.C && f.idx < f.items && f.si < f.spw;
         const long long step = (long long)(t0 + f.tl) * p.S + (long long)f.c * p.SC + f.s_lo + f.si;
-        return p.w + (real ? step * 64 : 0ll) + lane;
+        return real(f) ? p.w + step * 64 + lane : reinterpret_cast<const u32x4 *>(p.x);
     }
 };
 
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
     u32x4 ring[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-        ring[d] = __builtin_nontemporal_load(walk.addr(ld));
+        ring[d] = ring_refill(walk.addr(ld), u32x4{0u, 0u, 0u, 0u});
         walk.advance(ld);
     }
     {
@@ -223,7 +231,7 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                 if constexpr (!W16) {
                     const bf16x8 a0 = codes_to_bf16x8(wv.x, wv.y);
                     const bf16x8 a1 = codes_to_bf16x8(wv.z, wv.w);
-                    ring[d] = load_after_use(walk.addr(ld), wv);
+                    ring[d] = ring_refill(walk.addr(ld), wv);
                     walk.advance(ld);
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
@@ -242,7 +250,7 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                         acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0),
                                                                           acc[nb], 0, 0, 0);
                     }
-                    ring[d] = load_after_use(walk.addr(ld), wv);
+                    ring[d] = ring_refill(walk.addr(ld), wv);
                     walk.advance(ld);
                 }
                 if (in_range && si == cs.nsl - 1) {
@@ -391,7 +399,7 @@ __global__ __launch_bounds__(NW * 64) void stream_valu_kernel(const GemmParams p
     u32x4 ring[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-        ring[d] = __builtin_nontemporal_load(walk.addr(ld));
+        ring[d] = ring_refill(walk.addr(ld), u32x4{0u, 0u, 0u, 0u});
         walk.advance(ld);
     }
     lds_barrier();
@@ -428,7 +436,7 @@ __global__ __launch_bounds__(NW * 64) void stream_valu_kernel(const GemmParams p
                     wf[4 * q + 2] = (float)(signed char)((wd[q] >> 16) & 0xff);
                     wf[4 * q + 3] = (float)(signed char)(wd[q] >> 24);
                 }
-                ring[d] = load_after_use(walk.addr(ld), wv);
+                ring[d] = ring_refill(walk.addr(ld), wv);
                 walk.advance(ld);
                 const int k0 = (valid ? cs.s_lo + si : 0) * kStepK8 + 16 * g;
 #pragma unroll
