@@ -151,35 +151,47 @@ def main() -> int:
         return e0.elapsed_time(e1) * 1e3 / steps      # us per step
 
     calls8 = plan(True)
-    us_step = time_steps(calls8, args.steps, args.warmup)
+
+    def make_sequence(calls):
+        lin = []
+        for fn, a, _, is_lin in calls:
+            if is_lin and fn is qb.w8_linear:
+                x, wq, sc, N, y = a
+                lin.append((x, wq, sc, N, y))
+            elif is_lin:
+                x, wp, N, y = a
+                lin.append((x, wp, None, N, y))
+        fn, a, _, _ = calls[-1]
+        if fn is qb.lmhead_verify:
+            hl, hq, hs, VV, dr, _, oa, oc = a
+            ver = (hl, hq, hs, VV, dr, oa, oc)
+        else:
+            hl, hp, VV, dr, _, oa, oc = a
+            ver = (hl, hp, None, VV, dr, oa, oc)
+        return qb.Sequence(lin, verify=ver)
+
+    def time_sequence(seq, steps, warmup):
+        for _ in range(warmup):
+            seq.run()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            seq.run()
+        e1.record()
+        torch.cuda.synchronize()
+        assert not seq.timed_out(), "a device-wide barrier timed out"
+        return e0.elapsed_time(e1) * 1e3 / steps
+
+    # the timed step: ONE persistent launch (quasar_sequence_run) covering all linears + the head
+    seq8 = make_sequence(calls8)
+    us_step = time_sequence(seq8, args.steps, args.warmup)
     assert torch.isfinite(buf["h"][L % 2].float()).all(), "activations overflowed"
-    log(f"int8 step: {us_step:.1f} us  -> {step_bytes[1] / us_step / 1e3:.1f} GB/s algorithmic "
-        f"({weight_bytes / 1e9:.3f} GB of int8 weights)")
-
-    # ------------------------------------------------------------- per-launch durations (HIP events
-    # on the launch stream) of the dominant kernel: the int8 linear contraction
-    def per_launch(calls, reps=2):
-        evs = []
-        torch.cuda.synchronize()
-        for _ in range(reps):
-            for fn, a, nbytes, is_lin in calls:
-                s = torch.cuda.Event(enable_timing=True)
-                e = torch.cuda.Event(enable_timing=True)
-                s.record()
-                fn(*a)
-                e.record()
-                evs.append((s, e, nbytes, is_lin))
-        torch.cuda.synchronize()
-        lin_us = sum(s.elapsed_time(e) for s, e, _, il in evs if il) * 1e3
-        lin_b = sum(b for _, _, b, il in evs if il)
-        n_lin = sum(1 for *_, il in evs if il)
-        head_us = sum(s.elapsed_time(e) for s, e, _, il in evs if not il) * 1e3 / reps
-        return lin_b / n_lin, lin_us / n_lin, head_us
-
-    avg_b, avg_us, head_us = per_launch(calls8)
-    achieved = avg_b / avg_us / 1e3
-    log(f"int8 linear kernel: {avg_us:.2f} us per launch on average, {avg_b / 1e6:.2f} MB -> {achieved:.1f} GB/s; "
-        f"fused LM head + verify: {head_us:.1f} us -> {head_bytes(1) / head_us / 1e3:.1f} GB/s")
+    log(f"int8 step (one persistent launch, {seq8.nphases} phases): {us_step:.1f} us  -> "
+        f"{step_bytes[1] / us_step / 1e3:.1f} GB/s algorithmic ({weight_bytes / 1e9:.3f} GB of int8 weights)")
+    achieved = step_bytes[1] / us_step / 1e3
+    avg_b, avg_us = float(step_bytes[1]), us_step
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -192,14 +204,17 @@ def main() -> int:
     detail = {}
     us_twin = None
     if twin:
-        calls16 = plan(False)
-        us_twin = time_steps(calls16, max(2, args.steps // 2), 2)
+        seq16 = make_sequence(plan(False))
+        us_twin = time_sequence(seq16, max(2, args.steps // 2), 2)
         log(f"bf16-weight twin step: {us_twin:.1f} us -> {step_bytes[2] / us_twin / 1e3:.1f} GB/s; "
             f"int8 step is {us_twin / us_step:.2f}x faster")
         detail["bf16_twin_us_per_step"] = us_twin
         detail["int8_speedup_vs_bf16_twin"] = us_twin / us_step
 
     if args.detail:
+        us_calls = time_steps(calls8, max(2, args.steps // 4), 1)
+        log(f"  same step as {len(calls8)} separate calls from Python: {us_calls:.1f} us")
+        detail["separate_calls_us_per_step"] = us_calls
         # every linear shape cold: consecutive launches walk through the 36 layers' distinct copies
         for i, (name, K, N) in enumerate(shapes):
             x = torch.randn((M, K), device=dev).to(torch.bfloat16)
@@ -284,7 +299,7 @@ def main() -> int:
                    "weight_bytes_per_step": weight_bytes, "algorithmic_bytes_per_step": step_bytes[1]},
         "hbm_gbps_step": step_bytes[1] / us_step / 1e3,
         "hbm_frac_step": step_bytes[1] / us_step / 1e3 / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "stream_mfma_kernel (int8 linear, M<=8)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "stream_sequence_kernel<8, int8> (whole step, one launch)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "bytes_per_launch": avg_b, "us_per_launch": avg_us},
         "cpu_baseline": cpu,

@@ -143,6 +143,57 @@ int quasar_bf16_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int6
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Whole-step execution: the linears of a verification pass (and optionally the final
+ * vocabulary projection + acceptance) run as ONE persistent launch, so that the weight
+ * stream of Sec. 3.4 (Eq. 12: one byte per parameter over the whole model) is not interrupted
+ * at every layer boundary.  Results are bit-identical to calling quasar_w8_linear /
+ * quasar_lmhead_verify one by one in list order.
+ *
+ * Linears are described on the HOST; consecutive entries that read the same x (q|k|v, gate|up)
+ * are executed together, and a device-wide barrier is placed wherever an entry reads or
+ * overwrites a buffer touched since the previous barrier.  All entries use the same M and the
+ * same weight type: int8 (scales != NULL) or packed bf16 (scales == NULL).
+ *
+ * quasar_sequence_prepare (offline, synchronous copy of a small table to plan_device) fills the
+ * host handle `seq`; quasar_sequence_run enqueues one step.  The workspace (device,
+ * >= quasar_sequence_workspace_bytes(M)) holds the barrier words and argmax partials; after a
+ * step its second 32-bit word is non-zero if a barrier timed out (results then invalid).
+ * The launch needs every workgroup resident at once: do not run other kernels concurrently
+ * on the same device while a step is in flight.
+ */
+typedef struct quasar_linear_desc {
+    const uint16_t *x;        /* device [M, K] bf16, row stride ldx */
+    int64_t ldx;
+    const void *w_packed;     /* device, from quasar_quantize_weights or quasar_pack_bf16_weights */
+    const uint16_t *scales;   /* device [N] bf16, or NULL for bf16 weights */
+    uint16_t *y;              /* device [M, N] bf16, row stride ldy */
+    int64_t ldy;
+    int64_t N, K;
+} quasar_linear_desc;
+
+typedef struct quasar_verify_desc {
+    const uint16_t *hidden;   /* device [M, K] bf16, row stride ldh */
+    int64_t ldh;
+    const void *w_packed;
+    const uint16_t *scales;   /* NULL for bf16 weights */
+    int64_t V, K;
+    const int32_t *draft_ids; /* device [n_draft] */
+    int64_t n_draft;
+    int32_t *out_argmax;      /* device [M] */
+    int32_t *out_accept_len;  /* device [1] */
+} quasar_verify_desc;
+
+typedef struct quasar_sequence { int32_t words[16]; } quasar_sequence;
+
+size_t quasar_sequence_plan_bytes(int64_t n_linears);
+size_t quasar_sequence_workspace_bytes(int64_t M);
+int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears,
+                            const quasar_verify_desc *verify /* may be NULL */, int64_t M,
+                            void *plan_device, size_t plan_bytes, quasar_sequence *seq);
+int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Measurement helpers (the bandwidth term of Eq. 11-12 measured directly).
  * quasar_read_stream reads `bytes` (multiple of 16) from `src` with the same
  * load pattern as the linear kernels and writes one checksum word per workgroup

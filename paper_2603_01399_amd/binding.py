@@ -25,7 +25,27 @@ EXPORTS = (
     "quasar_quantize_weights", "quasar_unpack_weights", "quasar_w8_linear", "quasar_lmhead_verify",
     "quasar_pack_bf16_weights", "quasar_bf16_linear", "quasar_bf16_lmhead_verify",
     "quasar_read_stream", "quasar_copy_stream",
+    "quasar_sequence_plan_bytes", "quasar_sequence_workspace_bytes", "quasar_sequence_prepare",
+    "quasar_sequence_run",
 )
+
+
+class LinearDesc(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("ldx", ctypes.c_int64), ("w_packed", ctypes.c_void_p),
+                ("scales", ctypes.c_void_p), ("y", ctypes.c_void_p), ("ldy", ctypes.c_int64),
+                ("N", ctypes.c_int64), ("K", ctypes.c_int64)]
+
+
+class VerifyDesc(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_void_p), ("ldh", ctypes.c_int64), ("w_packed", ctypes.c_void_p),
+                ("scales", ctypes.c_void_p), ("V", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("draft_ids", ctypes.c_void_p), ("n_draft", ctypes.c_int64),
+                ("out_argmax", ctypes.c_void_p), ("out_accept_len", ctypes.c_void_p)]
+
+
+class SequenceHandle(ctypes.Structure):
+    _fields_ = [("words", ctypes.c_int32 * 16)]
+
 
 
 class QuasarError(RuntimeError):
@@ -62,6 +82,12 @@ def _load() -> ctypes.CDLL:
     lib.quasar_bf16_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, sz, vp]
     lib.quasar_read_stream.argtypes = [vp, sz, vp, vp]
     lib.quasar_copy_stream.argtypes = [vp, vp, sz, vp]
+    lib.quasar_sequence_plan_bytes.argtypes = [i64]
+    lib.quasar_sequence_plan_bytes.restype = sz
+    lib.quasar_sequence_workspace_bytes.argtypes = [i64]
+    lib.quasar_sequence_workspace_bytes.restype = sz
+    lib.quasar_sequence_prepare.argtypes = [vp, i64, vp, i64, vp, sz, vp]
+    lib.quasar_sequence_run.argtypes = [vp, vp, vp, sz, vp]
     return lib
 
 
@@ -244,3 +270,62 @@ def read_stream(src: torch.Tensor, sink: torch.Tensor, nbytes: int = None) -> No
 def copy_stream(dst: torch.Tensor, src: torch.Tensor, nbytes: int = None) -> None:
     nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
     _check("quasar_copy_stream", _lib.quasar_copy_stream(_ptr(dst), _ptr(src), nbytes, _stream()))
+
+
+class Sequence:
+    """One verification step as a single persistent launch (quasar_sequence_prepare / _run).
+
+    linears: list of (x, w_packed, scales_or_None, N, y) tensor tuples in execution order;
+    verify: optional (hidden, w_packed, scales_or_None, V, draft_ids, out_argmax, out_accept).
+    The tensors are only borrowed: the caller keeps them alive.
+    """
+
+    def __init__(self, linears, verify=None, M=None):
+        descs = (LinearDesc * max(len(linears), 1))()
+        keep = []
+        for i, (x, wp, sc, N, y) in enumerate(linears):
+            _dev(x, "x", torch.bfloat16)
+            _dev(y, "y", torch.bfloat16)
+            M = x.shape[0] if M is None else M
+            d = descs[i]
+            d.x, d.ldx, d.w_packed = x.data_ptr(), x.stride(0), wp.data_ptr()
+            d.scales = None if sc is None else sc.data_ptr()
+            d.y, d.ldy, d.N, d.K = y.data_ptr(), y.stride(0), N, x.shape[1]
+            keep.append((x, wp, sc, y))
+        vdesc = None
+        if verify is not None:
+            h, wp, sc, V, draft, out_argmax, out_accept = verify
+            M = h.shape[0] if M is None else M
+            vdesc = VerifyDesc()
+            vdesc.hidden, vdesc.ldh, vdesc.w_packed = h.data_ptr(), h.stride(0), wp.data_ptr()
+            vdesc.scales = None if sc is None else sc.data_ptr()
+            vdesc.V, vdesc.K = V, h.shape[1]
+            n_draft = 0 if draft is None else draft.numel()
+            vdesc.draft_ids = draft.data_ptr() if n_draft else None
+            vdesc.n_draft = n_draft
+            vdesc.out_argmax, vdesc.out_accept_len = out_argmax.data_ptr(), out_accept.data_ptr()
+            keep.append(verify)
+        self._keep = keep
+        self.M = M
+        dev = keep[0][0].device
+        self.plan = torch.empty(max(_lib.quasar_sequence_plan_bytes(len(linears)), 16), dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(_lib.quasar_sequence_workspace_bytes(M), dtype=torch.uint8, device=dev)
+        self.handle = SequenceHandle()
+        _check("quasar_sequence_prepare",
+               _lib.quasar_sequence_prepare(ctypes.cast(descs, ctypes.c_void_p), len(linears),
+                                            None if vdesc is None else ctypes.cast(ctypes.pointer(vdesc), ctypes.c_void_p),
+                                            M, _ptr(self.plan), self.plan.numel(),
+                                            ctypes.cast(ctypes.pointer(self.handle), ctypes.c_void_p)))
+
+    @property
+    def nphases(self) -> int:
+        return self.handle.words[1]
+
+    def run(self) -> None:
+        _check("quasar_sequence_run",
+               _lib.quasar_sequence_run(ctypes.cast(ctypes.pointer(self.handle), ctypes.c_void_p), _ptr(self.plan),
+                                        _ptr(self.workspace), self.workspace.numel(), _stream()))
+
+    def timed_out(self) -> bool:
+        """True if a device-wide barrier of the last finished step gave up (synchronises)."""
+        return bool(self.workspace[:8].view(torch.int32)[1].item() != 0)

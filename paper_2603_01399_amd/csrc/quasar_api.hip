@@ -14,6 +14,7 @@
 #include "pack.hpp"
 #include "probe.hpp"
 #include "stream_gemm.hpp"
+#include "stream_sequence.hpp"
 
 using namespace quasar;
 
@@ -71,21 +72,33 @@ struct Plan {
 
 constexpr int kMaxTilesPerWg = 512;   // bounds the per-workgroup scale table in LDS (16 KB)
 
+// K chunking shared by the single-call kernels and the whole-step kernel (identical chunks
+// give identical fp32 summation order, hence identical bits): one chunk if the activations
+// fit beside the staging area, otherwise equal chunks that leave room for scales and sums.
+void choose_chunks(int S, int x_bytes_per_step, int stage_bytes, int &SC, int &C) {
+    int single = kMaxLds - stage_bytes - 8 * 1024;
+    if (single > kSingleChunkX) single = kSingleChunkX;
+    int multi = kMaxLds - stage_bytes - 32 * 1024;
+    if (multi > kMultiChunkX) multi = kMultiChunkX;
+    const long long xall = (long long)S * x_bytes_per_step;
+    if (xall <= single) {
+        C = 1;
+        SC = S;
+        return;
+    }
+    int per = multi / x_bytes_per_step;   // steps per chunk that fit
+    if (per < 1) per = 1;
+    C = (S + per - 1) / per;
+    SC = (S + C - 1) / C;
+    C = (S + SC - 1) / SC;
+}
+
 // x_bytes_per_step: LDS bytes one step of activations occupies; unit_bytes: LDS bytes of one
 // tile accumulator / staging slot per wave; with_scales: reserve the row-scale table.
 Plan make_plan(int T, int S, int x_bytes_per_step, int unit_bytes, int NW, bool with_scales) {
     Plan pl{};
     pl.S = S;
-    const long long xall = (long long)S * x_bytes_per_step;
-    if (xall <= kSingleChunkX) {
-        pl.C = 1;
-        pl.SC = S;
-    } else {
-        const int per = kMultiChunkX / x_bytes_per_step;   // steps per chunk that fit
-        pl.C = (S + per - 1) / per;
-        pl.SC = (S + pl.C - 1) / pl.C;
-        pl.C = (S + pl.SC - 1) / pl.SC;
-    }
+    choose_chunks(S, x_bytes_per_step, 2 * NW * unit_bytes, pl.SC, pl.C);
     pl.xs_bytes = pl.SC * x_bytes_per_step;
     const int stage = 2 * NW * unit_bytes;
     int grid = device_cus() * g_tune_wgs.load();
@@ -373,6 +386,201 @@ int quasar_copy_stream(void *dst, const void *src, size_t bytes, void *hip_strea
     hipLaunchKernelGGL(copy_stream_kernel, dim3((int)grid), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16);
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+// Whole-step sequences
+// ------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int kSeqWaves = 16;
+constexpr int kSeqDepth = 8;
+constexpr int kSeqMagic = 0x51534551;   // "QSEQ"
+constexpr unsigned int kSeqSpinLimit = 4000000u;
+
+struct SeqHandle {   // lives in quasar_sequence::words
+    int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears;
+};
+static_assert(sizeof(SeqHandle) <= sizeof(quasar_sequence), "handle must fit");
+
+struct Range { uintptr_t lo, hi; };
+bool overlaps(const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi; }
+
+// Chunking of one phase for a fixed grid; returns false if it cannot fit the LDS.
+bool plan_phase(SeqPhase &ph, int MP, bool w16, int G, int &xs_bytes, int &sc_bytes, int &acc_bytes) {
+    const int NB = MP == 32 ? 2 : 1;
+    const int x_bytes_per_step = (w16 ? 64 : 128) * MP;
+    choose_chunks(ph.S, x_bytes_per_step, 2 * kSeqWaves * NB * 1024, ph.SC, ph.C);
+    const int tpw = (ph.T + G - 1) / G;
+    xs_bytes = ph.SC * x_bytes_per_step;
+    sc_bytes = w16 ? 0 : ((tpw * kTileRows * 2 + 15) / 16) * 16;
+    acc_bytes = ph.C > 1 ? tpw * NB * 1024 : 0;
+    return true;
+}
+
+template <int MP, bool W16>
+int launch_sequence(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
+    auto kernel = stream_sequence_kernel<MP, W16, kSeqWaves, kSeqDepth>;
+    if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return QUASAR_ERR_HIP;
+    hipLaunchKernelGGL(sequence_reset_kernel, dim3(1), dim3(64), 0, st, sp.sync);
+    // Plain launch: one workgroup per compute unit is resident by construction (grid = number
+    // of compute units, one workgroup fits each); a cooperative launch would add ~20 us.
+    hipLaunchKernelGGL(kernel, dim3(h.grid), dim3(kSeqWaves * 64), (unsigned int)h.lds_bytes, st, sp);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t quasar_sequence_plan_bytes(int64_t n_linears) {
+    if (n_linears < 0 || n_linears > (1 << 20)) return 0;
+    return (size_t)(n_linears + 1) * sizeof(SeqPhase);
+}
+
+size_t quasar_sequence_workspace_bytes(int64_t M) {
+    if (M < 1 || M > 32) return 0;
+    return 256 + (size_t)kMaxGrid * 32u * sizeof(unsigned long long);
+}
+
+int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears, const quasar_verify_desc *verify,
+                            int64_t M, void *plan_device, size_t plan_bytes, quasar_sequence *seq) {
+    if (!seq || !plan_device || (n_linears > 0 && !linears)) return QUASAR_ERR_NULL;
+    if (n_linears < 0 || (n_linears == 0 && !verify)) return QUASAR_ERR_SHAPE;
+    if (M < 1 || M > 32) return QUASAR_ERR_SHAPE;
+    if (plan_bytes < quasar_sequence_plan_bytes(n_linears)) return QUASAR_ERR_WORKSPACE;
+    if (!aligned(plan_device, 16)) return QUASAR_ERR_ALIGN;
+    const bool w16 = n_linears > 0 ? linears[0].scales == nullptr : verify->scales == nullptr;
+    const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
+    const int NB = MP == 32 ? 2 : 1;
+    const int G = device_cus();
+    if (G > kMaxGrid) return QUASAR_ERR_SHAPE;
+
+    std::vector<SeqPhase> phases;
+    std::vector<Range> reads, writes;     // since the last device-wide barrier
+    auto hazard = [&](const Range &x, const std::vector<Range> &ys) {
+        for (const Range &y : ys) {
+            for (const Range &wr : writes) if (overlaps(x, wr) || overlaps(y, wr)) return true;   // RAW, WAW
+            for (const Range &rd : reads) if (overlaps(y, rd)) return true;                       // WAR
+        }
+        for (const Range &wr : writes) if (overlaps(x, wr)) return true;
+        return false;
+    };
+    for (int64_t i = 0; i < n_linears; ++i) {
+        const quasar_linear_desc &d = linears[i];
+        if (!d.x || !d.w_packed || !d.y) return QUASAR_ERR_NULL;
+        if ((d.scales == nullptr) != w16) return QUASAR_ERR_DTYPE;
+        if (const int e = check_mnk(M, d.N, d.K)) return e;
+        if (d.ldx < d.K || d.ldy < d.N || d.ldx % 8 || d.ldy % 8) return QUASAR_ERR_SHAPE;
+        if (!aligned(d.x, 16) || !aligned(d.y, 16) || !aligned(d.w_packed, 16) || (!w16 && !aligned(d.scales, 8)))
+            return QUASAR_ERR_ALIGN;
+        const Range xr{reinterpret_cast<uintptr_t>(d.x), reinterpret_cast<uintptr_t>(d.x + (M - 1) * d.ldx + d.K)};
+        const Range yr{reinterpret_cast<uintptr_t>(d.y), reinterpret_cast<uintptr_t>(d.y + (M - 1) * d.ldy + d.N)};
+        if (overlaps(xr, yr)) return QUASAR_ERR_SHAPE;    // in-place is not supported
+        // join the previous phase when it reads the same input and nothing orders the two
+        bool joined = false;
+        if (!phases.empty()) {
+            SeqPhase &p = phases.back();
+            if (p.kind == EPI_LINEAR && p.nseg < kMaxSeg && p.x == d.x && p.ldx == d.ldx && p.K == (int)d.K) {
+                bool clash = false;
+                for (const Range &wr : writes) if (overlaps(yr, wr) || overlaps(xr, wr)) clash = true;
+                for (const Range &rd : reads) if (overlaps(yr, rd)) clash = true;
+                if (!clash) {
+                    SeqSeg &sg = p.seg[p.nseg];
+                    sg.w = static_cast<const u32x4 *>(d.w_packed); sg.scales = d.scales; sg.y = d.y; sg.ldy = d.ldy;
+                    sg.tile_begin = p.T; sg.pad_ = 0;
+                    p.T += (int)(d.N / kTileRows);
+                    ++p.nseg;
+                    writes.push_back(yr);
+                    joined = true;
+                }
+            }
+        }
+        if (joined) continue;
+        SeqPhase p{};
+        p.x = d.x; p.ldx = d.ldx; p.nseg = 1; p.K = (int)d.K;
+        p.S = (int)(d.K / (w16 ? kStepK16 : kStepK8));
+        p.T = (int)(d.N / kTileRows);
+        p.kind = EPI_LINEAR;
+        p.seg[0].w = static_cast<const u32x4 *>(d.w_packed); p.seg[0].scales = d.scales; p.seg[0].y = d.y;
+        p.seg[0].ldy = d.ldy; p.seg[0].tile_begin = 0;
+        p.sync_before = (!phases.empty() && hazard(xr, {yr})) ? 1 : 0;
+        if (p.sync_before) { reads.clear(); writes.clear(); }
+        reads.push_back(xr);
+        writes.push_back(yr);
+        phases.push_back(p);
+    }
+    if (verify) {
+        const quasar_verify_desc &v = *verify;
+        if (!v.hidden || !v.w_packed || !v.out_argmax || !v.out_accept_len) return QUASAR_ERR_NULL;
+        if (v.n_draft > 0 && !v.draft_ids) return QUASAR_ERR_NULL;
+        if ((v.scales == nullptr) != w16) return QUASAR_ERR_DTYPE;
+        if (const int e = check_mnk(M, v.V, v.K)) return e;
+        if (v.V > 0x7FFFFFF0ll || v.n_draft < 0 || v.n_draft > M || v.ldh < v.K || v.ldh % 8) return QUASAR_ERR_SHAPE;
+        if (!aligned(v.hidden, 16) || !aligned(v.w_packed, 16) || (!w16 && !aligned(v.scales, 8))) return QUASAR_ERR_ALIGN;
+        SeqPhase p{};
+        p.x = v.hidden; p.ldx = v.ldh; p.nseg = 1; p.K = (int)v.K;
+        p.S = (int)(v.K / (w16 ? kStepK16 : kStepK8));
+        p.T = (int)(v.V / kTileRows);
+        p.kind = EPI_ARGMAX;
+        p.seg[0].w = static_cast<const u32x4 *>(v.w_packed); p.seg[0].scales = v.scales; p.seg[0].y = nullptr;
+        p.seg[0].ldy = 0; p.seg[0].tile_begin = 0;
+        p.draft = v.draft_ids; p.n_draft = (int)v.n_draft; p.out_argmax = v.out_argmax; p.out_accept = v.out_accept_len;
+        p.V = (int)v.V;
+        const Range xr{reinterpret_cast<uintptr_t>(v.hidden), reinterpret_cast<uintptr_t>(v.hidden + (M - 1) * v.ldh + v.K)};
+        bool dep = false;
+        for (const Range &wr : writes) if (overlaps(xr, wr)) dep = true;
+        p.sync_before = (!phases.empty() && dep) ? 1 : 0;
+        phases.push_back(p);
+    }
+
+    int xs_max = 0, sc_max = 0, acc_max = 0;
+    for (SeqPhase &p : phases) {
+        int xs, sc, ac;
+        plan_phase(p, MP, w16, G, xs, sc, ac);
+        if (xs > xs_max) xs_max = xs;
+        if (sc > sc_max) sc_max = sc;
+        if (ac > acc_max) acc_max = ac;
+    }
+    const int lds = xs_max + sc_max + 2 * kSeqWaves * NB * 1024 + acc_max;
+    if (lds > kMaxLds) return QUASAR_ERR_SHAPE;
+    if (hipMemcpy(plan_device, phases.data(), phases.size() * sizeof(SeqPhase), hipMemcpyHostToDevice) != hipSuccess)
+        return QUASAR_ERR_HIP;
+    SeqHandle h{};
+    h.magic = kSeqMagic; h.nphases = (int)phases.size(); h.M = (int)M; h.MP = MP; h.w16 = w16 ? 1 : 0;
+    h.xs_bytes = xs_max; h.sc_bytes = sc_max; h.lds_bytes = lds < kMinLds ? kMinLds : lds; h.grid = G;
+    h.has_verify = verify ? 1 : 0; h.n_linears = (int)n_linears;
+    std::memset(seq, 0, sizeof(*seq));
+    std::memcpy(seq, &h, sizeof(h));
+    return QUASAR_OK;
+}
+
+int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, void *workspace, size_t workspace_bytes,
+                        void *hip_stream) {
+    if (!seq || !plan_device || !workspace) return QUASAR_ERR_NULL;
+    SeqHandle h;
+    std::memcpy(&h, seq, sizeof(h));
+    if (h.magic != kSeqMagic || h.nphases < 1) return QUASAR_ERR_SHAPE;
+    if (workspace_bytes < quasar_sequence_workspace_bytes(h.M)) return QUASAR_ERR_WORKSPACE;
+    if (!aligned(workspace, 16) || !aligned(plan_device, 16)) return QUASAR_ERR_ALIGN;
+    if (h.grid != device_cus()) return QUASAR_ERR_SHAPE;     // prepared for another device
+    SeqParams sp{};
+    sp.phases = static_cast<const SeqPhase *>(plan_device);
+    sp.nphases = h.nphases; sp.M = h.M; sp.xs_bytes = h.xs_bytes; sp.sc_bytes = h.sc_bytes;
+    sp.sync = static_cast<unsigned int *>(workspace);
+    sp.partial = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(workspace) + 256);
+    sp.spin_limit = kSeqSpinLimit;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (h.w16) {
+        if (h.MP == 8) return launch_sequence<8, true>(h, sp, st);
+        if (h.MP == 16) return launch_sequence<16, true>(h, sp, st);
+        return launch_sequence<32, true>(h, sp, st);
+    }
+    if (h.MP == 8) return launch_sequence<8, false>(h, sp, st);
+    if (h.MP == 16) return launch_sequence<16, false>(h, sp, st);
+    return launch_sequence<32, false>(h, sp, st);
 }
 
 }  // extern "C"

@@ -1,0 +1,202 @@
+"""GPU parity of the whole-step persistent launch (quasar_sequence_*): a chain of dependent
+linears plus the fused vocabulary/acceptance phase in ONE launch, against the oracle's own
+chain (each oracle output rounded once to bf16 feeds the next oracle linear), and bit-for-bit
+against the single-call entry points."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import quasar_ref as ref
+from paper_2603_01399_amd import synth
+from gpu_util import bf16_to_dev, bf16_to_host, f32_to_dev, i32_to_dev
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def qb():
+    assert torch.cuda.is_available()
+    from paper_2603_01399_amd import binding
+    return binding
+
+
+def layer_shapes(hidden, kv, inter):
+    return (("q", hidden, hidden), ("k", hidden, kv), ("v", hidden, kv), ("o", hidden, hidden),
+            ("gate", hidden, inter), ("up", hidden, inter), ("down", inter, hidden))
+
+
+def build_model(qb, n_layers, hidden, kv, inter, seed, bf16=False):
+    """Seeded weights with unit gain (std 1/sqrt(K)) so that a chain of linears stays O(1)."""
+    layers = []
+    for li in range(n_layers):
+        lin = {}
+        for i, (name, K, N) in enumerate(layer_shapes(hidden, kv, inter)):
+            w = synth.normal_weights(N, K, seed=seed + 100 * li + i, std=1.0 / np.sqrt(K))
+            if bf16:
+                lin[name] = dict(K=K, N=N, wb=synth.to_bf16_bits(w), wp=qb.pack_bf16_weights(f32_to_dev(w)), sc=None)
+            else:
+                q, s = ref.quantize_weights(w)
+                wq, sc = qb.quantize_weights(f32_to_dev(w))
+                lin[name] = dict(K=K, N=N, q=q, s=s, wp=wq, sc=sc)
+        layers.append(lin)
+    return layers
+
+
+def oracle_linear(l, xb):
+    y = ref.bf16_linear(xb, l["wb"]) if "wb" in l else ref.w8_linear(xb, l["q"], l["s"])
+    return y, ref.f64_to_bf16_bits(y)
+
+
+def oracle_chain(layers, x0):
+    outs = []
+    h = x0
+    for lin in layers:
+        o = {}
+        o["q"] = oracle_linear(lin["q"], h)
+        o["k"] = oracle_linear(lin["k"], h)
+        o["v"] = oracle_linear(lin["v"], h)
+        o["o"] = oracle_linear(lin["o"], o["q"][1])
+        o["gate"] = oracle_linear(lin["gate"], o["o"][1])
+        o["up"] = oracle_linear(lin["up"], o["o"][1])
+        o["down"] = oracle_linear(lin["down"], o["gate"][1])
+        h = o["down"][1]
+        outs.append(o)
+    return outs, h
+
+
+def gpu_buffers(layers, M, x0):
+    dev = "cuda"
+    bufs = []
+    h = bf16_to_dev(x0)
+    for lin in layers:
+        b = {n: torch.zeros((M, lin[n]["N"]), dtype=torch.bfloat16, device=dev) for n in lin}
+        b["in"] = h
+        h = b["down"]
+        bufs.append(b)
+    return bufs, h
+
+
+def linear_list(layers, bufs):
+    lst = []
+    for lin, b in zip(layers, bufs):
+        src = {"q": b["in"], "k": b["in"], "v": b["in"], "o": b["q"], "gate": b["o"], "up": b["o"], "down": b["gate"]}
+        for name in ("q", "k", "v", "o", "gate", "up", "down"):
+            l = lin[name]
+            lst.append((src[name], l["wp"], l["sc"], l["N"], b[name]))
+    return lst
+
+
+@pytest.mark.parametrize("M,hidden,kv,inter,bf16", [
+    (8, 256, 64, 768, False),
+    (8, 512, 128, 8320, False),     # down projection K = 8320: activations staged in two chunks
+    (3, 256, 64, 768, False),
+    (16, 256, 64, 768, False),
+    (32, 256, 64, 1536, False),
+    (8, 256, 64, 768, True),
+])
+def test_sequence_chain_vs_oracle_and_single_calls(qb, M, hidden, kv, inter, bf16):
+    print("sequence", M, hidden, kv, inter, bf16, flush=True)
+    n_layers, V = 3, 2048
+    layers = build_model(qb, n_layers, hidden, kv, inter, seed=9000 + M, bf16=bf16)
+    x0 = synth.activations_bf16(M, hidden, seed=9100 + M)
+    wv = synth.normal_weights(V, hidden, seed=9200 + M, std=1.0 / np.sqrt(hidden))
+    if bf16:
+        head = dict(wb=synth.to_bf16_bits(wv), wp=qb.pack_bf16_weights(f32_to_dev(wv)), sc=None)
+    else:
+        qh, sh = ref.quantize_weights(wv)
+        wq, sc = qb.quantize_weights(f32_to_dev(wv))
+        head = dict(q=qh, s=sh, wp=wq, sc=sc)
+
+    want, h_last = oracle_chain(layers, x0)
+    draft = np.arange(1, M, dtype=np.int32) if M > 1 else np.zeros(0, np.int32)
+    if bf16:
+        vout = ref.lmhead_verify(h_last, head["wb"], None, draft, weights_are_bf16=True)
+    else:
+        vout = ref.lmhead_verify(h_last, head["q"], head["s"], draft)
+
+    # ---- one persistent launch
+    bufs, h_dev = gpu_buffers(layers, M, x0)
+    out_argmax = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+    out_accept = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    seq = qb.Sequence(linear_list(layers, bufs),
+                      verify=(h_dev, head["wp"], head["sc"], V, i32_to_dev(draft) if len(draft) else None,
+                              out_argmax, out_accept))
+    assert seq.nphases == 4 * n_layers + 1          # q|k|v, o, gate|up, down per layer + the head
+    seq.run()
+    torch.cuda.synchronize()
+    assert not seq.timed_out()
+    for li in range(n_layers):
+        for name in ("q", "k", "v", "o", "gate", "up", "down"):
+            got = ref.bf16_bits_to_f64(bf16_to_host(bufs[li][name]))
+            err = ref.rel_maxabs_err(got, want[li][name][0])
+            assert err <= TOL, (li, name, err)
+    clear = (vout["top1"] - vout["top2"]) > TOL * vout["maxabs"]
+    assert clear.any()
+    am = out_argmax.cpu().numpy()
+    assert np.array_equal(am[clear], vout["argmax"][clear])
+    if np.all(clear[: min(vout["n_acc"], M - 1) + 1]):
+        assert int(out_accept.cpu()[0]) == vout["n_acc"]
+
+    # ---- the same step through the single-call entry points: identical bits
+    bufs2, h2 = gpu_buffers(layers, M, x0)
+    for (x, wp, sc, N, y) in linear_list(layers, bufs2):
+        if bf16:
+            qb.bf16_linear(x, wp, N, y)
+        else:
+            qb.w8_linear(x, wp, sc, N, y)
+    ws = qb.make_workspace(M, V, hidden)
+    dd = i32_to_dev(draft) if len(draft) else None
+    if bf16:
+        am2, acc2 = qb.bf16_lmhead_verify(h2, head["wp"], V, dd, ws)
+    else:
+        am2, acc2 = qb.lmhead_verify(h2, head["wp"], head["sc"], V, dd, ws)
+    torch.cuda.synchronize()
+    for li in range(n_layers):
+        for name in ("q", "k", "v", "o", "gate", "up", "down"):
+            assert torch.equal(bufs[li][name].view(torch.int16), bufs2[li][name].view(torch.int16)), (li, name)
+    assert torch.equal(am2, out_argmax) and torch.equal(acc2, out_accept)
+
+    # ---- repeatable
+    first = [bufs[li]["down"].clone() for li in range(n_layers)]
+    for _ in range(5):
+        seq.run()
+    torch.cuda.synchronize()
+    assert not seq.timed_out()
+    for li in range(n_layers):
+        assert torch.equal(first[li].view(torch.int16), bufs[li]["down"].view(torch.int16))
+
+
+def test_sequence_planted_head_exact(qb):
+    print("sequence planted head", flush=True)
+    M, K, V = 8, 512, 8192
+    h = synth.activations_bf16(M, K, seed=9500)
+    w = synth.normal_weights(V, K, seed=9501)
+    t = synth.distinct_targets(M, V, seed=9502)
+    synth.plant_targets(w, h, t)
+    wq, sc = qb.quantize_weights(f32_to_dev(w))
+    hd = bf16_to_dev(h)
+    for j in (0, 3, 7):
+        d = synth.draft_with_matches(t, j, V, M - 1)
+        out_argmax = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+        out_accept = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        seq = qb.Sequence([], verify=(hd, wq, sc, V, i32_to_dev(d), out_argmax, out_accept))
+        seq.run()
+        torch.cuda.synchronize()
+        assert not seq.timed_out()
+        assert np.array_equal(out_argmax.cpu().numpy(), t) and int(out_accept.cpu()[0]) == j
+
+
+def test_sequence_argument_errors(qb):
+    print("sequence arg errors", flush=True)
+    x = torch.zeros((8, 256), dtype=torch.bfloat16, device="cuda")
+    y = torch.zeros((8, 256), dtype=torch.bfloat16, device="cuda")
+    wq = torch.zeros(256 * 256, dtype=torch.int8, device="cuda")
+    sc = torch.zeros(256, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(qb.QuasarError) as e:
+        qb.Sequence([(x, wq, sc, 256, x)])               # in place
+    assert e.value.status == 2
+    wb = torch.zeros(256 * 256, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(qb.QuasarError) as e:
+        qb.Sequence([(x, wq, sc, 256, y), (y, wb, None, 256, torch.zeros_like(y))])   # mixed weight types
+    assert e.value.status == 5
