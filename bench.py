@@ -49,6 +49,9 @@ def main() -> int:
     import numpy as np
     import torch
     from paper_2603_01399_amd import binding as qb, synth
+    if os.environ.get("QUASAR_BENCH_LIB"):           # A/B runs of alternative builds of the library
+        qb.LIB_PATH = os.environ["QUASAR_BENCH_LIB"]
+        qb._lib = qb._load()
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
@@ -85,17 +88,13 @@ def main() -> int:
     ws = qb.make_workspace(M, V, H)
     out_argmax = torch.empty(M, dtype=torch.int32, device=dev)
     out_accept = torch.empty(1, dtype=torch.int32, device=dev)
-    # activation buffers, allocated once: the dataflow of a decoder layer with the non-linear
-    # parts left out (o reads q's output, gate/up read o's, down reads gate's, next layer reads down's)
-    buf = {
-        "h": [torch.empty((M, H), dtype=torch.bfloat16, device=dev) for _ in range(2)],
-        "q": torch.empty((M, 4096), dtype=torch.bfloat16, device=dev),
-        "k": torch.empty((M, 1024), dtype=torch.bfloat16, device=dev),
-        "v": torch.empty((M, 1024), dtype=torch.bfloat16, device=dev),
-        "o": torch.empty((M, 4096), dtype=torch.bfloat16, device=dev),
-        "g": torch.empty((M, 12288), dtype=torch.bfloat16, device=dev),
-        "u": torch.empty((M, 12288), dtype=torch.bfloat16, device=dev),
-    }
+    # activation buffers, allocated once, one set per layer (every buffer is written once per
+    # step): the dataflow of a decoder layer with the non-linear parts left out - o reads q's
+    # output, gate/up read o's, down reads gate's, the next layer reads down's
+    def new(n):
+        return torch.empty((M, n), dtype=torch.bfloat16, device=dev)
+    bufs = [{"q": new(4096), "k": new(1024), "v": new(1024), "o": new(4096), "g": new(12288), "u": new(12288),
+             "d": new(H)} for _ in range(L)]
     torch.cuda.synchronize()
     log(f"setup: {L} layers + LM head resident in {time.time() - t_setup:.1f} s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
@@ -113,18 +112,18 @@ def main() -> int:
         """The launches of one step as (fn, args, algorithmic bytes, is_linear)."""
         calls = []
         for li, lin in enumerate(layers):
-            hin = h0 if li == 0 else buf["h"][li % 2]        # every step starts from the same hidden state
-            hout = buf["h"][(li + 1) % 2]
-            io = {"q_proj": (hin, buf["q"]), "k_proj": (hin, buf["k"]), "v_proj": (hin, buf["v"]),
-                  "o_proj": (buf["q"], buf["o"]), "gate_proj": (buf["o"], buf["g"]),
-                  "up_proj": (buf["o"], buf["u"]), "down_proj": (buf["g"], hout)}
+            hin = h0 if li == 0 else bufs[li - 1]["d"]       # every step starts from the same hidden state
+            bf = bufs[li]
+            io = {"q_proj": (hin, bf["q"]), "k_proj": (hin, bf["k"]), "v_proj": (hin, bf["v"]),
+                  "o_proj": (bf["q"], bf["o"]), "gate_proj": (bf["o"], bf["g"]),
+                  "up_proj": (bf["o"], bf["u"]), "down_proj": (bf["g"], bf["d"])}
             for name, K, N, wq, sc, wp in lin:
                 x, y = io[name]
                 if int8:
                     calls.append((qb.w8_linear, (x, wq, sc, N, y), lin_bytes(K, N, 1), True))
                 else:
                     calls.append((qb.bf16_linear, (x, wp, N, y), lin_bytes(K, N, 2), True))
-        hlast = buf["h"][L % 2]
+        hlast = bufs[L - 1]["d"]
         if int8:
             calls.append((qb.lmhead_verify, (hlast, head_q, head_s, V, draft, ws, out_argmax, out_accept),
                           head_bytes(1), False))
@@ -187,8 +186,9 @@ def main() -> int:
     # the timed step: ONE persistent launch (quasar_sequence_run) covering all linears + the head
     seq8 = make_sequence(calls8)
     us_step = time_sequence(seq8, args.steps, args.warmup)
-    assert torch.isfinite(buf["h"][L % 2].float()).all(), "activations overflowed"
-    log(f"int8 step (one persistent launch, {seq8.nphases} phases): {us_step:.1f} us  -> "
+    assert torch.isfinite(bufs[L - 1]["d"].float()).all(), "activations overflowed"
+    log(f"int8 step (one persistent launch, {seq8.nphases} phases, {seq8.n_data_waits} data waits, "
+        f"{seq8.n_barriers} barriers): {us_step:.1f} us  -> "
         f"{step_bytes[1] / us_step / 1e3:.1f} GB/s algorithmic ({weight_bytes / 1e9:.3f} GB of int8 weights)")
     achieved = step_bytes[1] / us_step / 1e3
     avg_b, avg_us = float(step_bytes[1]), us_step

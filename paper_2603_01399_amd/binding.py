@@ -321,6 +321,16 @@ class Sequence:
     def nphases(self) -> int:
         return self.handle.words[1]
 
+    @property
+    def n_barriers(self) -> int:
+        """Phases that wait at a device-wide barrier (inputs in reused or partially overlapping buffers)."""
+        return self.handle.words[12]
+
+    @property
+    def n_data_waits(self) -> int:
+        """Phases that wait for their input by polling the data itself (write-once buffers)."""
+        return self.handle.words[13]
+
     def run(self) -> None:
         _check("quasar_sequence_run",
                _lib.quasar_sequence_run(ctypes.cast(ctypes.pointer(self.handle), ctypes.c_void_p), _ptr(self.plan),

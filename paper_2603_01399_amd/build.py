@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 vector instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the whole-step kernel keeps rarely executed phase-entry code inside a fully unrolled round;
+    # without this the compiler silently refuses "#pragma unroll" once that body grows
+    "-mllvm", "-pragma-unroll-threshold=1000000",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
 ]
 

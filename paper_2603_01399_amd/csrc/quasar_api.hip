@@ -396,12 +396,16 @@ int quasar_copy_stream(void *dst, const void *src, size_t bytes, void *hip_strea
 namespace {
 
 constexpr int kSeqWaves = 16;
-constexpr int kSeqDepth = 8;
+#ifndef QUASAR_SEQ_DEPTH
+#define QUASAR_SEQ_DEPTH 8
+#endif
+constexpr int kSeqDepth = QUASAR_SEQ_DEPTH;
 constexpr int kSeqMagic = 0x51534551;   // "QSEQ"
 constexpr unsigned int kSeqSpinLimit = 4000000u;
 
 struct SeqHandle {   // lives in quasar_sequence::words
-    int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears;
+    int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears, arm_blocks;
+    int n_barriers, n_data_waits;
 };
 static_assert(sizeof(SeqHandle) <= sizeof(quasar_sequence), "handle must fit");
 
@@ -424,7 +428,7 @@ template <int MP, bool W16>
 int launch_sequence(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
     auto kernel = stream_sequence_kernel<MP, W16, kSeqWaves, kSeqDepth>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return QUASAR_ERR_HIP;
-    hipLaunchKernelGGL(sequence_reset_kernel, dim3(1), dim3(64), 0, st, sp.sync);
+    hipLaunchKernelGGL(sequence_arm_kernel, dim3(h.arm_blocks), dim3(256), 0, st, sp.phases, sp.nphases, sp.M, sp.sync);
     // Plain launch: one workgroup per compute unit is resident by construction (grid = number
     // of compute units, one workgroup fits each); a cooperative launch would add ~20 us.
     hipLaunchKernelGGL(kernel, dim3(h.grid), dim3(kSeqWaves * 64), (unsigned int)h.lds_bytes, st, sp);
@@ -459,14 +463,41 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
     if (G > kMaxGrid) return QUASAR_ERR_SHAPE;
 
     std::vector<SeqPhase> phases;
+    // every output written so far in the sequence: (range, phase, segment, N, ldy, pointer)
+    struct Out { Range r; int ph, seg; long long N, ldy; const uint16_t *y; int writes; };
+    std::vector<Out> outs;
     std::vector<Range> reads, writes;     // since the last device-wide barrier
-    auto hazard = [&](const Range &x, const std::vector<Range> &ys) {
-        for (const Range &y : ys) {
-            for (const Range &wr : writes) if (overlaps(x, wr) || overlaps(y, wr)) return true;   // RAW, WAW
-            for (const Range &rd : reads) if (overlaps(y, rd)) return true;                       // WAR
+    // How does a phase reading `xr` (and writing `yrs`) have to wait?
+    //   - nothing it touches was touched since the last barrier            -> SEQ_WAIT_NONE
+    //   - its input is exactly one earlier output that is written only once in the whole
+    //     sequence, and its outputs clash with nothing                      -> SEQ_WAIT_DATA
+    //   - anything else (partial overlaps, reused buffers, write hazards)   -> SEQ_WAIT_BARRIER
+    auto classify = [&](const uint16_t *x, long long ldx, long long K, const Range &xr,
+                        const std::vector<Range> &yrs, int *producer) -> int {
+        *producer = -1;
+        bool write_clash = false, raw = false;
+        for (const Range &y : yrs) {
+            for (const Range &wr : writes) if (overlaps(y, wr)) write_clash = true;
+            for (const Range &rd : reads) if (overlaps(y, rd)) write_clash = true;
         }
-        for (const Range &wr : writes) if (overlaps(x, wr)) return true;
-        return false;
+        for (const Range &wr : writes) if (overlaps(xr, wr)) raw = true;
+        if (write_clash) return SEQ_WAIT_BARRIER;
+        if (!raw) return SEQ_WAIT_NONE;
+        int hits = 0, which = -1;
+        for (size_t i = 0; i < outs.size(); ++i)
+            if (overlaps(xr, outs[i].r)) { ++hits; which = (int)i; }
+        if (hits == 1 && outs[which].y == x && outs[which].ldy == ldx && outs[which].N == K &&
+            outs[which].writes == 1) {
+            *producer = which;
+            return SEQ_WAIT_DATA;
+        }
+        return SEQ_WAIT_BARRIER;
+    };
+    auto note_output = [&](const Range &yr, int ph, int seg, long long N, long long ldy, const uint16_t *y) {
+        int n = 1;
+        for (Out &o : outs)
+            if (overlaps(o.r, yr)) { ++o.writes; n = o.writes; }
+        outs.push_back(Out{yr, ph, seg, N, ldy, y, n});
     };
     for (int64_t i = 0; i < n_linears; ++i) {
         const quasar_linear_desc &d = linears[i];
@@ -480,37 +511,47 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
         const Range yr{reinterpret_cast<uintptr_t>(d.y), reinterpret_cast<uintptr_t>(d.y + (M - 1) * d.ldy + d.N)};
         if (overlaps(xr, yr)) return QUASAR_ERR_SHAPE;    // in-place is not supported
         // join the previous phase when it reads the same input and nothing orders the two
-        bool joined = false;
         if (!phases.empty()) {
             SeqPhase &p = phases.back();
             if (p.kind == EPI_LINEAR && p.nseg < kMaxSeg && p.x == d.x && p.ldx == d.ldx && p.K == (int)d.K) {
                 bool clash = false;
-                for (const Range &wr : writes) if (overlaps(yr, wr) || overlaps(xr, wr)) clash = true;
+                // (the shared input is already waited for by the phase being joined)
+                for (const Range &wr : writes) if (overlaps(yr, wr)) clash = true;
                 for (const Range &rd : reads) if (overlaps(yr, rd)) clash = true;
+                for (const Out &o : outs) if (overlaps(o.r, yr)) clash = true;   // keeps outputs single-assignment
                 if (!clash) {
                     SeqSeg &sg = p.seg[p.nseg];
                     sg.w = static_cast<const u32x4 *>(d.w_packed); sg.scales = d.scales; sg.y = d.y; sg.ldy = d.ldy;
-                    sg.tile_begin = p.T; sg.pad_ = 0;
+                    sg.tile_begin = p.T; sg.N = (int)d.N; sg.arm = 0; sg.pad_ = 0;
                     p.T += (int)(d.N / kTileRows);
+                    note_output(yr, (int)phases.size() - 1, p.nseg, d.N, d.ldy, d.y);
                     ++p.nseg;
                     writes.push_back(yr);
-                    joined = true;
+                    continue;
                 }
             }
         }
-        if (joined) continue;
         SeqPhase p{};
         p.x = d.x; p.ldx = d.ldx; p.nseg = 1; p.K = (int)d.K;
         p.S = (int)(d.K / (w16 ? kStepK16 : kStepK8));
         p.T = (int)(d.N / kTileRows);
         p.kind = EPI_LINEAR;
         p.seg[0].w = static_cast<const u32x4 *>(d.w_packed); p.seg[0].scales = d.scales; p.seg[0].y = d.y;
-        p.seg[0].ldy = d.ldy; p.seg[0].tile_begin = 0;
-        p.sync_before = (!phases.empty() && hazard(xr, {yr})) ? 1 : 0;
-        if (p.sync_before) { reads.clear(); writes.clear(); }
+        p.seg[0].ldy = d.ldy; p.seg[0].tile_begin = 0; p.seg[0].N = (int)d.N;
+        int producer = -1;
+        p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(d.x, d.ldx, d.K, xr, {yr}, &producer);
+        if (p.wait == SEQ_WAIT_BARRIER) { reads.clear(); writes.clear(); }
+        if (p.wait == SEQ_WAIT_DATA) phases[outs[producer].ph].seg[outs[producer].seg].arm = 1;
         reads.push_back(xr);
         writes.push_back(yr);
+        note_output(yr, (int)phases.size(), 0, d.N, d.ldy, d.y);
         phases.push_back(p);
+    }
+    // an output that turned out to be written more than once must not be waited for by its data
+    for (SeqPhase &p : phases) {
+        if (p.wait != SEQ_WAIT_DATA) continue;
+        for (const Out &o : outs)
+            if (o.y == p.x && o.writes > 1) p.wait = SEQ_WAIT_BARRIER;
     }
     if (verify) {
         const quasar_verify_desc &v = *verify;
@@ -526,15 +567,27 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
         p.T = (int)(v.V / kTileRows);
         p.kind = EPI_ARGMAX;
         p.seg[0].w = static_cast<const u32x4 *>(v.w_packed); p.seg[0].scales = v.scales; p.seg[0].y = nullptr;
-        p.seg[0].ldy = 0; p.seg[0].tile_begin = 0;
+        p.seg[0].ldy = 0; p.seg[0].tile_begin = 0; p.seg[0].N = (int)v.V;
         p.draft = v.draft_ids; p.n_draft = (int)v.n_draft; p.out_argmax = v.out_argmax; p.out_accept = v.out_accept_len;
         p.V = (int)v.V;
         const Range xr{reinterpret_cast<uintptr_t>(v.hidden), reinterpret_cast<uintptr_t>(v.hidden + (M - 1) * v.ldh + v.K)};
-        bool dep = false;
-        for (const Range &wr : writes) if (overlaps(xr, wr)) dep = true;
-        p.sync_before = (!phases.empty() && dep) ? 1 : 0;
+        int producer = -1;
+        p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(v.hidden, v.ldh, v.K, xr, {}, &producer);
+        if (p.wait == SEQ_WAIT_DATA) {
+            if (outs[producer].writes > 1) p.wait = SEQ_WAIT_BARRIER;
+            else phases[outs[producer].ph].seg[outs[producer].seg].arm = 1;
+        }
         phases.push_back(p);
     }
+    // a segment is armed only if every consumer that waits for its data is still in that mode
+    for (SeqPhase &p : phases)
+        for (int sgi = 0; sgi < p.nseg; ++sgi) {
+            if (!p.seg[sgi].arm) continue;
+            bool used = false;
+            for (const SeqPhase &c : phases)
+                if (c.wait == SEQ_WAIT_DATA && c.x == p.seg[sgi].y) used = true;
+            if (!used) p.seg[sgi].arm = 0;
+        }
 
     int xs_max = 0, sc_max = 0, acc_max = 0;
     for (SeqPhase &p : phases) {
@@ -552,6 +605,11 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
     h.magic = kSeqMagic; h.nphases = (int)phases.size(); h.M = (int)M; h.MP = MP; h.w16 = w16 ? 1 : 0;
     h.xs_bytes = xs_max; h.sc_bytes = sc_max; h.lds_bytes = lds < kMinLds ? kMinLds : lds; h.grid = G;
     h.has_verify = verify ? 1 : 0; h.n_linears = (int)n_linears;
+    h.arm_blocks = 1;
+    for (const SeqPhase &p : phases)
+        for (int sgi = 0; sgi < p.nseg; ++sgi) if (p.seg[sgi].arm) h.arm_blocks = 128;
+    h.n_barriers = 0; h.n_data_waits = 0;
+    for (const SeqPhase &p : phases) { if (p.wait == SEQ_WAIT_BARRIER) ++h.n_barriers; if (p.wait == SEQ_WAIT_DATA) ++h.n_data_waits; }
     std::memset(seq, 0, sizeof(*seq));
     std::memcpy(seq, &h, sizeof(h));
     return QUASAR_OK;

@@ -4,12 +4,18 @@
 // Why: a single verification linear streams 4-50 MB, i.e. 1-8 microseconds of HBM time, while
 // a kernel boundary costs several microseconds of launch, first-load latency and drain.  Inside
 // one persistent kernel the weight stream never stops: weight addresses do not depend on the
-// activations, so every wave's load ring runs ahead into the next phase while the workgroups
-// meet at a grid barrier and re-stage the new activations.
+// activations, so every wave's load ring runs ahead into the following phases while the
+// workgroups wait for the activations of the next phase.
 //
 // A phase is a group of linears that share their input (q|k|v, gate|up) and therefore need no
 // ordering among themselves; its weight tiles are numbered across the member matrices
 // ("segments") and split evenly over the workgroups.
+//
+// Each wave walks ONE flat sequence of slots over the whole step:
+//     for phase, for K chunk, for tile of this workgroup, for step of this wave's K slice
+// (at least one slot per tile so that all waves meet at every tile end).  Slot j is loaded
+// into ring[j % D] exactly D slots before it is consumed, with no padding between phases, so
+// the ring always holds D real weight loads, many of them belonging to later phases.
 #pragma once
 
 #include "stream_gemm.hpp"
@@ -18,12 +24,20 @@ namespace quasar {
 
 constexpr int kMaxSeg = 4;
 
+enum { SEQ_WAIT_NONE = 0, SEQ_WAIT_BARRIER = 1, SEQ_WAIT_DATA = 2 };
+
+// bf16 bit pattern that the epilogue never produces (NaN results are canonicalised to 0x7FC0):
+// marks "not written yet" in activation buffers that are handed from phase to phase
+constexpr unsigned int kNotYet16 = 0xFFFFu;
+
 struct SeqSeg {
     const u32x4 *w;          // packed weights of this member matrix
     const uint16_t *scales;  // [N] (nullptr for bf16 weights)
     uint16_t *y;             // [M, N] output, row stride ldy
     long long ldy;
     int tile_begin;          // index of the segment's first tile inside the phase
+    int N;
+    int arm;                 // y is consumed through SEQ_WAIT_DATA: pre-filled with kNotYet16
     int pad_;
 };
 
@@ -35,7 +49,7 @@ struct SeqPhase {
     int T;                   // tiles over all segments
     int K, S, SC, C;         // as in GemmParams
     int kind;                // EPI_LINEAR or EPI_ARGMAX (argmax: one segment)
-    int sync_before;         // the input is produced by an earlier phase of this launch
+    int wait;                // SEQ_WAIT_*: how the input becomes available
     const int32_t *draft;
     int32_t *out_argmax;
     int32_t *out_accept;
@@ -60,13 +74,13 @@ struct SeqParams {
     int sc_bytes;            // LDS reserved for row scales (max over phases)
     unsigned int *sync;      // [0] arrival counter (zero at launch), [1] error flag (zero at launch)
     unsigned long long *partial;   // argmax phase: [gridDim.x][MP] packed (logit, index) keys
-    unsigned int spin_limit; // bound on barrier polling iterations
+    unsigned int spin_limit; // bound on polling iterations
 };
 
-// Data that crosses a grid barrier inside the launch (outputs of one phase read as the input
-// of a later one, argmax partials) is written and read with device-coherent accesses that go
-// past the per-XCD L2 caches.  That makes cache write-back / invalidate at the barrier
-// unnecessary; on this part those maintenance operations cost more than the barrier itself.
+// Data that crosses from one phase to a later one inside the launch (outputs read as the
+// input of a later phase, argmax partials) is written and read with device-coherent accesses
+// that go past the per-XCD L2 caches.  That makes cache write-back / invalidate unnecessary;
+// on this part those maintenance operations cost more than the barrier itself.
 __device__ __forceinline__ void coherent_store_u64(void *p, unsigned long long v) {
     __hip_atomic_store(as_global(static_cast<unsigned long long *>(p)), v, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
@@ -80,11 +94,18 @@ __device__ __forceinline__ u32x4 coherent_load_u32x4(const void *p) {
     const unsigned long long hi = coherent_load_u64(static_cast<const unsigned long long *>(p) + 1);
     return u32x4{(unsigned int)lo, (unsigned int)(lo >> 32), (unsigned int)hi, (unsigned int)(hi >> 32)};
 }
+__device__ __forceinline__ bool has_not_yet(const u32x4 &v) {
+    bool r = false;
+    const unsigned int wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r = r || (wd[i] & 0xFFFFu) == kNotYet16 || (wd[i] >> 16) == kNotYet16;
+    return r;
+}
 
 // All workgroups of the launch meet.  Every wave first waits until its own (coherent) stores
 // have been acknowledged, so whatever the workgroup wrote is readable device-wide once the
 // arrival counter has been bumped.  Polling is bounded: on timeout the error flag is raised
-// and every later barrier falls through, so the grid always drains.
+// and every later wait falls through, so the grid always drains.
 __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int target, unsigned int spin_limit) {
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     lds_barrier();
@@ -97,11 +118,21 @@ __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int ta
                 __hip_atomic_store(as_global(&sync[1]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
-            __builtin_amdgcn_s_sleep(1);
+            __builtin_amdgcn_s_sleep(8);
         }
     }
     lds_barrier();
 }
+
+#ifdef QUASAR_SEQ_TRACE
+// development aid: workgroups 0 and 100 record the shader clock at a few points of every phase
+#define QUASAR_TRACE(slot)                                                                          \
+    if ((b == 0 || b == 100) && tid == 0 && c_ph < 400)                                              \
+        reinterpret_cast<unsigned long long *>(sp.partial)[65536 + ((b ? 1 : 0) * 400 + c_ph) * 8 + (slot)] = \
+            __builtin_readcyclecounter();
+#else
+#define QUASAR_TRACE(slot)
+#endif
 
 template <int MP, bool W16, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParams sp) {
@@ -112,14 +143,15 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
     constexpr int XB = 4;
     constexpr int nthreads = NW * 64;
-
     static_assert(NW == 16, "the in-kernel second stage of the verify phase assumes 1024 threads");
+
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, mcol = lane & 15;
     const int G = gridDim.x, b = blockIdx.x;
     const int M = sp.M;
+    const int nph = sp.nphases;
     const const_phase_ptr phases = (const_phase_ptr)(unsigned long long)sp.phases;
 
     u32x4 *xs = reinterpret_cast<u32x4 *>(lds);
@@ -127,49 +159,6 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     f32x4 *stage = reinterpret_cast<f32x4 *>(lds + sp.xs_bytes + sp.sc_bytes);   // [2][NW][NB][64]
     f32x4 *accs = stage + 2 * NW * NB * 64;                                      // [ntiles][NB][64] (C > 1)
 
-    // ---- position in the (phase, chunk, tile, step) sequence of this wave
-    struct Front {
-        int ph, c, idx, tl, si;          // position
-        int t0, ntiles;                  // this workgroup's tile range in phase ph
-        int s_lo, spw, nsl, items, padded;
-    };
-    auto tile_range = [&](const auto &P, int &t0, int &ntiles) {
-        t0 = (int)(((long long)P.T * b) / G);
-        ntiles = (int)(((long long)P.T * (b + 1)) / G) - t0;
-    };
-    auto slice = [&](const auto &P, Front &f) {
-        const int scc = min(P.SC, P.S - f.c * P.SC);
-        f.s_lo = (scc * w) / NW;
-        f.spw = (scc * (w + 1)) / NW - f.s_lo;
-        f.nsl = max(f.spw, 1);
-        f.items = f.ntiles * f.nsl;
-        f.padded = ((f.items + D - 1) / D) * D;
-    };
-    // skip forward over (phase, chunk) pairs that have no slots for this workgroup
-    auto settle = [&](Front &f) {
-        while (f.ph < sp.nphases) {
-            const auto &P = phases[f.ph];
-            if (f.c == 0) tile_range(P, f.t0, f.ntiles);
-            if (f.c < P.C) {
-                slice(P, f);
-                if (f.padded > 0) return;
-                ++f.c;
-            } else {
-                ++f.ph;
-                f.c = 0;
-            }
-        }
-        f.items = 0; f.padded = 0; f.spw = 0; f.nsl = 1; f.ntiles = 0;
-    };
-    auto advance = [&](Front &f) {
-        ++f.idx;
-        ++f.si;
-        if (f.si >= f.nsl) { f.si = 0; ++f.tl; }
-        if (f.idx >= f.padded && f.ph < sp.nphases) {
-            ++f.c; f.idx = 0; f.tl = 0; f.si = 0;
-            settle(f);
-        }
-    };
     auto seg_of = [&](const auto &P, int t) -> int {
         int s = 0;
         if (P.nseg > 1 && t >= P.seg[1].tile_begin) s = 1;
@@ -177,34 +166,124 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
         if (P.nseg > 3 && t >= P.seg[3].tile_begin) s = 3;
         return s;
     };
-    auto is_real = [&](const Front &f) -> bool {
-        return f.ph < sp.nphases && f.idx < f.items && f.si < f.spw;
-    };
-    auto w_addr = [&](const Front &f) -> const u32x4 * {
-        if (!is_real(f)) return reinterpret_cast<const u32x4 *>(phases[0].x);   // one hot line
-        const auto &P = phases[f.ph];
-        const int t = f.t0 + f.tl;
+
+    // ------------------------------------------------------------------ load front
+    // everything the per-slot path needs lives in registers; the phase table is read only
+    // when the front enters a new (phase, chunk) or crosses into another member matrix
+    int l_ph = 0, l_c = -1, l_tl = 0, l_si = 0, l_nsl = 1, l_spw = 0, l_ntiles = 0, l_t0 = 0, l_seg_end = 0;
+    int l_s_lo = 0;
+    long long l_stride = 0;
+    const u32x4 *l_wt = nullptr;
+    auto l_retile = [&]() {
+        const auto &P = phases[l_ph];
+        const int t = l_t0 + l_tl;
         const int s = seg_of(P, t);
-        const long long step = (long long)(t - P.seg[s].tile_begin) * P.S + (long long)f.c * P.SC + f.s_lo + f.si;
-        return P.seg[s].w + step * 64 + lane;
+        l_seg_end = (s + 1 < P.nseg) ? P.seg[s + 1].tile_begin : P.T;
+        l_stride = (long long)P.S * 64;
+        l_wt = P.seg[s].w + ((long long)(t - P.seg[s].tile_begin) * P.S + (long long)l_c * P.SC + l_s_lo) * 64;
+    };
+    // move to the next (phase, chunk) in which this workgroup has tiles
+    auto l_next = [&]() {
+        for (;;) {
+            ++l_c;
+            if (l_ph < nph && l_c >= phases[l_ph].C) { ++l_ph; l_c = 0; }
+            if (l_ph >= nph) { l_ntiles = 0; l_spw = 0; l_nsl = 1; return; }
+            const auto &P = phases[l_ph];
+            l_t0 = (int)(((long long)P.T * b) / G);
+            l_ntiles = (int)(((long long)P.T * (b + 1)) / G) - l_t0;
+            if (l_ntiles == 0) { l_c = P.C - 1; continue; }
+            const int scc = min(P.SC, P.S - l_c * P.SC);
+            l_s_lo = (scc * w) / NW;
+            l_spw = (scc * (w + 1)) / NW - l_s_lo;
+            l_nsl = max(l_spw, 1);
+            l_tl = 0;
+            l_si = 0;
+            l_retile();
+            return;
+        }
+    };
+    auto l_advance = [&]() {
+        if (l_ph >= nph) return;
+        if (++l_si < l_nsl) return;
+        l_si = 0;
+        if (++l_tl < l_ntiles) {
+            if (l_t0 + l_tl == l_seg_end) l_retile(); else l_wt += l_stride;
+            return;
+        }
+        l_next();
+    };
+    auto l_addr = [&]() -> const u32x4 * {
+        const bool real = l_ph < nph && l_si < l_spw;
+        // slots without a step read one hot, read-only line (never the line of the barrier words)
+        return real ? l_wt + (long long)l_si * 64 + lane : reinterpret_cast<const u32x4 *>(sp.phases);
     };
 
-    // ---- staging of one activation chunk and of the row scales of this workgroup's tiles
-    auto x_stage = [&](const auto &P, int c) {
+    l_next();
+    u32x4 ring[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        ring[d] = ring_refill(l_addr(), u32x4{0u, 0u, 0u, 0u});
+        l_advance();
+    }
+
+    // ------------------------------------------------------------------ compute front
+    int c_ph = 0, c_c = -1, c_tl = 0, c_si = 0, c_nsl = 1, c_spw = 0, c_ntiles = 0, c_t0 = 0, c_s_lo = 0;
+    int c_C = 1, c_kind = EPI_LINEAR;
+    // output segment of the current tile, kept in registers so that the tile-end path reads
+    // nothing from the phase table
+    uint16_t *c_y = nullptr;
+    long long c_ldy = 0;
+    int c_tb = 0, c_seg_end = 0;
+    auto c_reseg = [&]() {
+        const auto &P = phases[c_ph];
+        const int s = seg_of(P, c_t0 + c_tl);
+        c_y = P.seg[s].y;
+        c_ldy = P.seg[s].ldy;
+        c_tb = P.seg[s].tile_begin;
+        c_seg_end = (s + 1 < P.nseg) ? P.seg[s + 1].tile_begin : P.T;
+    };
+    bool need_enter = true;
+    unsigned int barriers_done = 0;
+    int parity = 0;
+    f32x4 acc[NB];
+    float bestv[NB];
+    unsigned int besti[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        bestv[nb] = -__builtin_inff();
+        besti[nb] = 0x7FFFFFFFu;
+    }
+    const int xm = (MP == 8) ? (mcol & 7) : mcol;
+
+    // stage one activation chunk; with SEQ_WAIT_DATA the loads are repeated until no element
+    // carries the "not written yet" pattern any more
+    auto x_stage = [&](const auto &P, int c, bool poll) {
         const int scc = min(P.SC, P.S - c * P.SC);
         const int npieces = scc * PPS * MP;
         for (int base = 0; base < npieces; base += nthreads * XB) {
             u32x4 v[XB];
+            unsigned int spins = 0;
+            for (;;) {
+                bool again = false;
 #pragma unroll
-            for (int i = 0; i < XB; ++i) {
-                const int idx = base + i * nthreads + tid;
-                v[i] = u32x4{0u, 0u, 0u, 0u};
-                if (idx < npieces) {
-                    const int m = idx & (MP - 1), p8 = idx >> LMP;
-                    if (m < M) {
-                        const long long k = (long long)c * P.SC * KSTEP + 8ll * p8;
-                        v[i] = coherent_load_u32x4(P.x + m * P.ldx + k);
+                for (int i = 0; i < XB; ++i) {
+                    const int idx = base + i * nthreads + tid;
+                    v[i] = u32x4{0u, 0u, 0u, 0u};
+                    if (idx < npieces) {
+                        const int m = idx & (MP - 1), p8 = idx >> LMP;
+                        if (m < M) {
+                            const long long k = (long long)c * P.SC * KSTEP + 8ll * p8;
+                            v[i] = coherent_load_u32x4(P.x + m * P.ldx + k);
+                            again = again || (poll && has_not_yet(v[i]));
+                        }
                     }
+                }
+                if (!again) break;
+                if (++spins > sp.spin_limit ||
+                    __hip_atomic_load(as_global(&sp.sync[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                    __hip_atomic_store(as_global(&sp.sync[1]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
                 }
             }
 #pragma unroll
@@ -225,214 +304,247 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             }
         }
     };
-
-    Front ld;
-    ld.ph = 0; ld.c = 0; ld.idx = 0; ld.tl = 0; ld.si = 0;
-    settle(ld);
-
-    u32x4 ring[D];
-#pragma unroll
-    for (int d = 0; d < D; ++d) {
-        ring[d] = ring_refill(w_addr(ld), u32x4{0u, 0u, 0u, 0u});
-        advance(ld);
-    }
-
-    f32x4 acc[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    int parity = 0;
-    unsigned int barriers_done = 0;
-    const int xm = (MP == 8) ? (mcol & 7) : mcol;
-
-    for (int ph = 0; ph < sp.nphases; ++ph) {
+    // end of a phase: publish argmax partials and run the second stage
+    auto phase_end = [&](int ph) {
         const auto &P = phases[ph];
-        int t0, ntiles;
-        tile_range(P, t0, ntiles);
-        if (P.sync_before) {
-            ++barriers_done;
-            grid_barrier(sp.sync, barriers_done * (unsigned int)G, sp.spin_limit);
-        } else {
-            lds_barrier();   // the previous phase's last epilogue has read its scales
-        }
-        scale_stage(P, t0, ntiles);
-        float bestv[NB];
-        unsigned int besti[NB];
+        if (P.kind != EPI_ARGMAX) return;
+        unsigned long long *red = reinterpret_cast<unsigned long long *>(stage);   // [NW][MP]
+        lds_barrier();
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) { bestv[nb] = -__builtin_inff(); besti[nb] = 0x7FFFFFFFu; }
-
-        for (int c = 0; c < P.C; ++c) {
-            if (ntiles > 0) {
-                x_stage(P, c);
+        for (int nb = 0; nb < NB; ++nb) {
+            unsigned long long key = argmax_key(bestv[nb], besti[nb]);
+            unsigned long long o = shfl_xor_u64(key, 16);
+            key = o > key ? o : key;
+            o = shfl_xor_u64(key, 32);
+            key = o > key ? o : key;
+            if (g == 0 && (MP != 8 || mcol < 8)) red[w * MP + mcol + 16 * nb] = key;
+            bestv[nb] = -__builtin_inff();
+            besti[nb] = 0x7FFFFFFFu;
+        }
+        lds_barrier();
+        if (tid < MP) {
+            unsigned long long key = red[tid];
+            for (int ww = 1; ww < NW; ++ww) {
+                const unsigned long long o = red[ww * MP + tid];
+                key = o > key ? o : key;
             }
+            coherent_store_u64(sp.partial + (long long)b * MP + tid, key);
+        }
+        ++barriers_done;
+        grid_barrier(sp.sync, barriers_done * (unsigned int)G, sp.spin_limit);
+        if (b == 0) {
+            int32_t *am = reinterpret_cast<int32_t *>(stage);
+            const int m = tid >> 5, sub = tid & 31;
+            unsigned long long key = 0ull;
+            if (m < M)
+                for (int i0 = sub; i0 < G; i0 += 32 * 8) {
+                    unsigned long long o[8];   // eight independent loads in flight per lane
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int i = i0 + 32 * u;
+                        o[u] = i < G ? coherent_load_u64(sp.partial + (long long)i * MP + m) : 0ull;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) key = o[u] > key ? o[u] : key;
+                }
+#pragma unroll
+            for (int off = 16; off >= 1; off >>= 1) {
+                const unsigned long long o = shfl_xor_u64(key, off);
+                key = o > key ? o : key;
+            }
+            if (m < M && sub == 0) {
+                unsigned int idx = argmax_key_index(key);
+                if (idx >= (unsigned int)P.V) idx = 0;
+                am[m] = (int32_t)idx;
+                *as_global(P.out_argmax + m) = (int32_t)idx;
+            }
+            lds_barrier();
+            if (tid == 0) {
+                int n = 0;
+                while (n < P.n_draft && am[n] == *as_global(P.draft + n)) ++n;
+                *as_global(P.out_accept) = n;
+            }
+            lds_barrier();
+        }
+    };
+    // enter the next (phase, chunk): take part in the phase's wait, stage scales and
+    // activations.  Returns false when the sequence is finished.
+    auto c_enter = [&]() -> bool {
+        for (;;) {
+            ++c_c;
+            if (c_ph < nph && c_c >= c_C) {
+                phase_end(c_ph);
+                ++c_ph;
+                c_c = 0;
+            }
+            if (c_ph >= nph) return false;
+            const auto &P = phases[c_ph];
+            if (c_c == 0) {
+                QUASAR_TRACE(0)
+                c_C = P.C;
+                c_kind = P.kind;
+                c_t0 = (int)(((long long)P.T * b) / G);
+                c_ntiles = (int)(((long long)P.T * (b + 1)) / G) - c_t0;
+                if (P.wait == SEQ_WAIT_BARRIER) {
+                    ++barriers_done;
+                    grid_barrier(sp.sync, barriers_done * (unsigned int)G, sp.spin_limit);
+                } else {
+                    lds_barrier();   // the previous phase's last epilogue has read its scales
+                }
+                if (c_ntiles == 0) { c_c = c_C - 1; continue; }   // nothing to do here but the waits
+                scale_stage(P, c_t0, c_ntiles);
+            }
+            const int scc = min(P.SC, P.S - c_c * P.SC);
+            c_s_lo = (scc * w) / NW;
+            c_spw = (scc * (w + 1)) / NW - c_s_lo;
+            c_nsl = max(c_spw, 1);
+            c_tl = 0;
+            c_si = 0;
+            c_reseg();
+            QUASAR_TRACE(1)
+            x_stage(P, c_c, P.wait == SEQ_WAIT_DATA);
+            QUASAR_TRACE(2)
             // known-empty load queue: keeps the counted waits of the ring exact (see stream_gemm.hpp)
             __builtin_amdgcn_s_waitcnt(0x0F70);
+            QUASAR_TRACE(3)
             lds_barrier();
-            Front cs;
-            cs.c = c; cs.t0 = t0; cs.ntiles = ntiles;
-            slice(P, cs);
-            int tl = 0, si = 0;
-            const int rounds = cs.padded / D;
-            for (int r = 0; r < rounds; ++r) {
-#pragma unroll
-                for (int d = 0; d < D; ++d) {
-                    const int idx = r * D + d;
-                    const bool in_range = idx < cs.items;
-                    const bool valid = in_range && si < cs.spw;
-                    u32x4 wv = ring[d];
-                    if (!valid) wv = u32x4{0u, 0u, 0u, 0u};
-                    const int piece0 = (valid ? cs.s_lo + si : 0) * PPS;
-                    if constexpr (!W16) {
-                        const bf16x8 a0 = codes_to_bf16x8(wv.x, wv.y);
-                        const bf16x8 a1 = codes_to_bf16x8(wv.z, wv.w);
-                        ring[d] = ring_refill(w_addr(ld), wv);
-                        advance(ld);
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) {
-                            const u32x4 b0 = xs[(piece0 + 2 * g) * MP + xm + 16 * nb];
-                            const u32x4 b1 = xs[(piece0 + 2 * g + 1) * MP + xm + 16 * nb];
-                            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0),
-                                                                              acc[nb], 0, 0, 0);
-                            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1),
-                                                                              acc[nb], 0, 0, 0);
-                        }
-                    } else {
-                        const bf16x8 a0 = __builtin_bit_cast(bf16x8, wv);
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) {
-                            const u32x4 b0 = xs[(piece0 + g) * MP + xm + 16 * nb];
-                            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0),
-                                                                              acc[nb], 0, 0, 0);
-                        }
-                        ring[d] = ring_refill(w_addr(ld), wv);
-                        advance(ld);
-                    }
-                    if (in_range && si == cs.nsl - 1) {
-                        f32x4 *st = stage + (parity * NW) * NB * 64;
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) {
-                            st[(w * NB + nb) * 64 + lane] = acc[nb];
-                            acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-                        }
-                        lds_barrier();
-                        if (w == (tl % NW)) {
-                            f32x4 rsum[NB];
-#pragma unroll
-                            for (int nb = 0; nb < NB; ++nb) {
-                                rsum[nb] = st[nb * 64 + lane];
-#pragma unroll
-                                for (int ww = 1; ww < NW; ++ww) rsum[nb] += st[(ww * NB + nb) * 64 + lane];
-                                if (P.C > 1) {
-                                    f32x4 *a = accs + (tl * NB + nb) * 64 + lane;
-                                    if (c > 0) rsum[nb] += *a;
-                                    if (c < P.C - 1) *a = rsum[nb];
-                                }
-                            }
-                            if (c == P.C - 1) {
-                                const int t = t0 + tl;
-                                const int s = seg_of(P, t);
-                                const int n0 = (t - P.seg[s].tile_begin) * kTileRows + 4 * g;
-                                float s4[4] = {1.f, 1.f, 1.f, 1.f};
-                                if constexpr (!W16) {
-                                    const u32x2 sb =
-                                        *reinterpret_cast<const u32x2 *>(sc_lds + tl * kTileRows + 4 * g);
-                                    s4[0] = bf16_bits_to_float(sb.x & 0xFFFFu);
-                                    s4[1] = bf16_bits_to_float(sb.x >> 16);
-                                    s4[2] = bf16_bits_to_float(sb.y & 0xFFFFu);
-                                    s4[3] = bf16_bits_to_float(sb.y >> 16);
-                                }
-#pragma unroll
-                                for (int nb = 0; nb < NB; ++nb) {
-                                    const int m = mcol + 16 * nb;
-                                    const float v0 = rsum[nb].x * s4[0], v1 = rsum[nb].y * s4[1];
-                                    const float v2 = rsum[nb].z * s4[2], v3 = rsum[nb].w * s4[3];
-                                    if (P.kind == EPI_LINEAR) {
-                                        if (m < M) {
-                                            u32x2 o;
-                                            o.x = float_to_bf16_bits(v0) | (float_to_bf16_bits(v1) << 16);
-                                            o.y = float_to_bf16_bits(v2) | (float_to_bf16_bits(v3) << 16);
-                                            coherent_store_u64(P.seg[s].y + m * P.seg[s].ldy + n0,
-                                                               (unsigned long long)o.x | ((unsigned long long)o.y << 32));
-                                        }
-                                    } else {
-                                        if (v0 > bestv[nb]) { bestv[nb] = v0; besti[nb] = n0; }
-                                        if (v1 > bestv[nb]) { bestv[nb] = v1; besti[nb] = n0 + 1; }
-                                        if (v2 > bestv[nb]) { bestv[nb] = v2; besti[nb] = n0 + 2; }
-                                        if (v3 > bestv[nb]) { bestv[nb] = v3; besti[nb] = n0 + 3; }
-                                    }
-                                }
-                            }
-                        }
-                        parity ^= 1;
-                    }
-                    if (in_range) {
-                        ++si;
-                        if (si >= cs.nsl) { si = 0; ++tl; }
-                    }
-                }
-            }
+            QUASAR_TRACE(4)
+            return true;
         }
+    };
 
-        if (P.kind == EPI_ARGMAX) {
-            unsigned long long *red = reinterpret_cast<unsigned long long *>(stage);   // [NW][MP]
-            lds_barrier();
+    // The rare phase/chunk entry code is inlined into every slot of the unrolled round (the
+    // build raises the compiler's pragma-unroll size limit for this): any other shape - a side
+    // exit from the round, or re-entering it through a switch - makes the compiler lose count of
+    // the outstanding ring loads and drain the ring.  After the last phase the rest of the
+    // round consumes empty slots.
+    bool running = true;
+    while (running) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                unsigned long long key = argmax_key(bestv[nb], besti[nb]);
-                unsigned long long o = shfl_xor_u64(key, 16);
-                key = o > key ? o : key;
-                o = shfl_xor_u64(key, 32);
-                key = o > key ? o : key;
-                if (g == 0 && (MP != 8 || mcol < 8)) red[w * MP + mcol + 16 * nb] = key;
-            }
-            lds_barrier();
-            if (tid < MP) {
-                unsigned long long key = red[tid];
-                for (int ww = 1; ww < NW; ++ww) {
-                    const unsigned long long o = red[ww * MP + tid];
-                    key = o > key ? o : key;
+        for (int d = 0; d < D; ++d) {
+            if (__builtin_expect(need_enter, 0)) {
+                need_enter = false;
+                if (!c_enter()) {
+                    running = false;
+                    c_spw = 0;
+                    c_si = 0;
+                    c_nsl = 0x7FFFFFFF;
                 }
-                coherent_store_u64(sp.partial + (long long)b * MP + tid, key);
             }
-            ++barriers_done;
-            grid_barrier(sp.sync, barriers_done * (unsigned int)G, sp.spin_limit);
-            if (b == 0) {
-                // second stage on one workgroup: combine the per-workgroup keys, count draft matches
-                int32_t *am = reinterpret_cast<int32_t *>(stage);
-                const int t32 = tid & 1023;
-                const int m = t32 >> 5, sub = t32 & 31;
-                unsigned long long key = 0ull;
-                if (tid < 1024 && m < M)
-                    for (int i = sub; i < G; i += 32) {
-                        const unsigned long long o = coherent_load_u64(sp.partial + (long long)i * MP + m);
-                        key = o > key ? o : key;
+            const bool valid = c_si < c_spw;
+            u32x4 wv = ring[d];
+            if (!valid) wv = u32x4{0u, 0u, 0u, 0u};
+            const int piece0 = (valid ? c_s_lo + c_si : 0) * PPS;
+            if constexpr (!W16) {
+                const bf16x8 a0 = codes_to_bf16x8(wv.x, wv.y);
+                const bf16x8 a1 = codes_to_bf16x8(wv.z, wv.w);
+                ring[d] = ring_refill(l_addr(), wv);
+                l_advance();
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const u32x4 b0 = xs[(piece0 + 2 * g) * MP + xm + 16 * nb];
+                    const u32x4 b1 = xs[(piece0 + 2 * g + 1) * MP + xm + 16 * nb];
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb],
+                                                                      0, 0, 0);
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1), acc[nb],
+                                                                      0, 0, 0);
+                }
+            } else {
+                const bf16x8 a0 = __builtin_bit_cast(bf16x8, wv);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const u32x4 b0 = xs[(piece0 + g) * MP + xm + 16 * nb];
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb],
+                                                                      0, 0, 0);
+                }
+                ring[d] = ring_refill(l_addr(), wv);
+                l_advance();
+            }
+            if (c_si == c_nsl - 1) {
+                // ---- tile end: cross-wave sum through LDS, fixed order
+                f32x4 *st = stage + (parity * NW) * NB * 64;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    st[(w * NB + nb) * 64 + lane] = acc[nb];
+                    acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+                lds_barrier();
+                if (w == (c_tl % NW)) {
+                    f32x4 rsum[NB];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        rsum[nb] = st[nb * 64 + lane];
+#pragma unroll
+                        for (int ww = 1; ww < NW; ++ww) rsum[nb] += st[(ww * NB + nb) * 64 + lane];
+                        if (c_C > 1) {
+                            f32x4 *a = accs + (c_tl * NB + nb) * 64 + lane;
+                            if (c_c > 0) rsum[nb] += *a;
+                            if (c_c < c_C - 1) *a = rsum[nb];
+                        }
                     }
+                    if (c_c == c_C - 1) {
+                        const int n0 = (c_t0 + c_tl - c_tb) * kTileRows + 4 * g;
+                        float s4[4] = {1.f, 1.f, 1.f, 1.f};
+                        if constexpr (!W16) {
+                            const u32x2 sb = *reinterpret_cast<const u32x2 *>(sc_lds + c_tl * kTileRows + 4 * g);
+                            s4[0] = bf16_bits_to_float(sb.x & 0xFFFFu);
+                            s4[1] = bf16_bits_to_float(sb.x >> 16);
+                            s4[2] = bf16_bits_to_float(sb.y & 0xFFFFu);
+                            s4[3] = bf16_bits_to_float(sb.y >> 16);
+                        }
 #pragma unroll
-                for (int off = 16; off >= 1; off >>= 1) {
-                    const unsigned long long o = shfl_xor_u64(key, off);
-                    key = o > key ? o : key;
+                        for (int nb = 0; nb < NB; ++nb) {
+                            const int m = mcol + 16 * nb;
+                            const float v0 = rsum[nb].x * s4[0], v1 = rsum[nb].y * s4[1];
+                            const float v2 = rsum[nb].z * s4[2], v3 = rsum[nb].w * s4[3];
+                            if (c_kind == EPI_LINEAR) {
+                                if (m < M) {
+                                    const unsigned long long lo =
+                                        float_to_bf16_bits(v0) | (float_to_bf16_bits(v1) << 16);
+                                    const unsigned long long hi =
+                                        float_to_bf16_bits(v2) | (float_to_bf16_bits(v3) << 16);
+                                    coherent_store_u64(c_y + m * c_ldy + n0, lo | (hi << 32));
+                                }
+                            } else {
+                                if (v0 > bestv[nb]) { bestv[nb] = v0; besti[nb] = n0; }
+                                if (v1 > bestv[nb]) { bestv[nb] = v1; besti[nb] = n0 + 1; }
+                                if (v2 > bestv[nb]) { bestv[nb] = v2; besti[nb] = n0 + 2; }
+                                if (v3 > bestv[nb]) { bestv[nb] = v3; besti[nb] = n0 + 3; }
+                            }
+                        }
+                    }
                 }
-                if (tid < 1024 && m < M && sub == 0) {
-                    unsigned int idx = argmax_key_index(key);
-                    if (idx >= (unsigned int)P.V) idx = 0;
-                    am[m] = (int32_t)idx;
-                    *as_global(P.out_argmax + m) = (int32_t)idx;
-                }
-                lds_barrier();
-                if (tid == 0) {
-                    int n = 0;
-                    while (n < P.n_draft && am[n] == *as_global(P.draft + n)) ++n;
-                    *as_global(P.out_accept) = n;
-                }
-                lds_barrier();
+                parity ^= 1;
+            }
+            // advance the compute front
+            if (++c_si >= c_nsl) {
+                c_si = 0;
+                if (++c_tl >= c_ntiles) { need_enter = true; QUASAR_TRACE(5) }
+                else if (__builtin_expect(c_t0 + c_tl == c_seg_end, 0)) c_reseg();
             }
         }
     }
 }
 
-// Clears the two sync words ahead of a sequence launch (a kernel rather than a memset so that
-// callers may capture the call sequence in a graph).
-__global__ void sequence_reset_kernel(unsigned int *sync) {
-    if (threadIdx.x < 2) sync[threadIdx.x] = 0u;
+// Clears the two sync words ahead of a sequence launch and pre-fills the activation buffers
+// that are handed from phase to phase with the "not written yet" pattern (kernels rather
+// than memsets so that callers may capture the call sequence in a graph).
+__global__ __launch_bounds__(256) void sequence_arm_kernel(const SeqPhase *phases, int nphases, int M,
+                                                           unsigned int *sync) {
+    if (blockIdx.x == 0 && threadIdx.x < 2) sync[threadIdx.x] = 0u;
+    for (int ph = 0; ph < nphases; ++ph) {
+        const SeqPhase &P = phases[ph];
+        for (int s = 0; s < P.nseg; ++s) {
+            if (!P.seg[s].arm) continue;
+            const long long n4 = (long long)P.seg[s].N / 4;         // 8-byte units per row
+            const long long total = n4 * M;
+            for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total;
+                 i += (long long)gridDim.x * 256) {
+                const long long m = i / n4, j = i - m * n4;
+                *reinterpret_cast<unsigned long long *>(P.seg[s].y + m * P.seg[s].ldy + 4 * j) = ~0ull;
+            }
+        }
+    }
 }
 
 }  // namespace quasar

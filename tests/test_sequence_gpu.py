@@ -123,6 +123,8 @@ def test_sequence_chain_vs_oracle_and_single_calls(qb, M, hidden, kv, inter, bf1
                       verify=(h_dev, head["wp"], head["sc"], V, i32_to_dev(draft) if len(draft) else None,
                               out_argmax, out_accept))
     assert seq.nphases == 4 * n_layers + 1          # q|k|v, o, gate|up, down per layer + the head
+    # every buffer is written once: all dependent phases wait for their data, none at a barrier
+    assert seq.n_barriers == 0 and seq.n_data_waits == 4 * n_layers
     seq.run()
     torch.cuda.synchronize()
     assert not seq.timed_out()
@@ -165,6 +167,42 @@ def test_sequence_chain_vs_oracle_and_single_calls(qb, M, hidden, kv, inter, bf1
     assert not seq.timed_out()
     for li in range(n_layers):
         assert torch.equal(first[li].view(torch.int16), bufs[li]["down"].view(torch.int16))
+
+
+def test_sequence_reused_buffers_fall_back_to_barriers(qb):
+    """Ping-pong activation buffers (written more than once per step) must be ordered by
+    device-wide barriers; results stay identical to the single-call path."""
+    print("sequence ping-pong", flush=True)
+    M, H, L = 8, 512, 6
+    ws = []
+    for i in range(L):
+        w = synth.normal_weights(H, H, seed=9700 + i, std=1.0 / np.sqrt(H))
+        ws.append((ref.quantize_weights(w), qb.quantize_weights(f32_to_dev(w))))
+    x0 = synth.activations_bf16(M, H, seed=9750)
+    xd = bf16_to_dev(x0)
+    pp = [torch.zeros((M, H), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    lin = []
+    for i in range(L):
+        src = xd if i == 0 else pp[i % 2]
+        lin.append((src, ws[i][1][0], ws[i][1][1], H, pp[(i + 1) % 2]))
+    seq = qb.Sequence(lin)
+    assert seq.n_barriers >= L - 2 and seq.nphases == L
+    for _ in range(3):
+        seq.run()
+    torch.cuda.synchronize()
+    assert not seq.timed_out()
+    h = x0
+    for i in range(L):
+        y = ref.w8_linear(h, ws[i][0][0], ws[i][0][1])
+        h = ref.f64_to_bf16_bits(y)
+    got = ref.bf16_bits_to_f64(bf16_to_host(pp[L % 2]))
+    assert ref.rel_maxabs_err(got, y) <= TOL
+    ref_out = [torch.zeros((M, H), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    for i in range(L):
+        src = xd if i == 0 else ref_out[i % 2]
+        qb.w8_linear(src, ws[i][1][0], ws[i][1][1], H, ref_out[(i + 1) % 2])
+    torch.cuda.synchronize()
+    assert torch.equal(ref_out[L % 2].view(torch.int16), pp[L % 2].view(torch.int16))
 
 
 def test_sequence_planted_head_exact(qb):
