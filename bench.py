@@ -187,7 +187,7 @@ def main() -> int:
     seq8 = make_sequence(calls8)
     us_step = time_sequence(seq8, args.steps, args.warmup)
     assert torch.isfinite(bufs[L - 1]["d"].float()).all(), "activations overflowed"
-    log(f"int8 step (one persistent launch, {seq8.nphases} phases, {seq8.n_data_waits} data waits, "
+    log(f"int8 step (one persistent launch, {seq8.nphases} phases, {seq8.n_flag_waits} flag waits, "
         f"{seq8.n_barriers} barriers): {us_step:.1f} us  -> "
         f"{step_bytes[1] / us_step / 1e3:.1f} GB/s algorithmic ({weight_bytes / 1e9:.3f} GB of int8 weights)")
     achieved = step_bytes[1] / us_step / 1e3

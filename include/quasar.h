@@ -150,14 +150,19 @@ int quasar_bf16_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int6
  * quasar_lmhead_verify one by one in list order.
  *
  * Linears are described on the HOST; consecutive entries that read the same x (q|k|v, gate|up)
- * are executed together, and a device-wide barrier is placed wherever an entry reads or
- * overwrites a buffer touched since the previous barrier.  All entries use the same M and the
- * same weight type: int8 (scales != NULL) or packed bf16 (scales == NULL).
+ * are executed together.  An entry whose input is the output of earlier entries waits for
+ * those entries only (per-workgroup completion flags) provided every buffer involved is
+ * written once per step; buffers that are written more than once per step (ping-pong reuse)
+ * or partially overwritten are ordered by a device-wide barrier instead, which is slower.
+ * All entries use the same M and the same weight type: int8 (scales != NULL) or packed bf16
+ * (scales == NULL).
  *
- * quasar_sequence_prepare (offline, synchronous copy of a small table to plan_device) fills the
- * host handle `seq`; quasar_sequence_run enqueues one step.  The workspace (device,
- * >= quasar_sequence_workspace_bytes(M)) holds the barrier words and argmax partials; after a
- * step its second 32-bit word is non-zero if a barrier timed out (results then invalid).
+ * quasar_sequence_prepare (offline and synchronous: copies a small table to plan_device and
+ * clears the workspace) fills the host handle `seq`; quasar_sequence_run enqueues one step.
+ * The workspace (device, >= quasar_sequence_workspace_bytes(n_linears, M)) belongs to this
+ * sequence from prepare on: it holds barrier words, completion flags and argmax partials and
+ * must not be shared or modified between steps.  After a step its second 32-bit word is
+ * non-zero if a wait timed out (results then invalid).
  * The launch needs every workgroup resident at once: do not run other kernels concurrently
  * on the same device while a step is in flight.
  */
@@ -186,10 +191,11 @@ typedef struct quasar_verify_desc {
 typedef struct quasar_sequence { int32_t words[16]; } quasar_sequence;
 
 size_t quasar_sequence_plan_bytes(int64_t n_linears);
-size_t quasar_sequence_workspace_bytes(int64_t M);
+size_t quasar_sequence_workspace_bytes(int64_t n_linears, int64_t M);
 int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears,
                             const quasar_verify_desc *verify /* may be NULL */, int64_t M,
-                            void *plan_device, size_t plan_bytes, quasar_sequence *seq);
+                            void *plan_device, size_t plan_bytes,
+                            void *workspace, size_t workspace_bytes, quasar_sequence *seq);
 int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device,
                         void *workspace, size_t workspace_bytes, void *hip_stream);
 

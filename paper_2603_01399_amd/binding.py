@@ -84,9 +84,9 @@ def _load() -> ctypes.CDLL:
     lib.quasar_copy_stream.argtypes = [vp, vp, sz, vp]
     lib.quasar_sequence_plan_bytes.argtypes = [i64]
     lib.quasar_sequence_plan_bytes.restype = sz
-    lib.quasar_sequence_workspace_bytes.argtypes = [i64]
+    lib.quasar_sequence_workspace_bytes.argtypes = [i64, i64]
     lib.quasar_sequence_workspace_bytes.restype = sz
-    lib.quasar_sequence_prepare.argtypes = [vp, i64, vp, i64, vp, sz, vp]
+    lib.quasar_sequence_prepare.argtypes = [vp, i64, vp, i64, vp, sz, vp, sz, vp]
     lib.quasar_sequence_run.argtypes = [vp, vp, vp, sz, vp]
     return lib
 
@@ -309,12 +309,14 @@ class Sequence:
         self.M = M
         dev = keep[0][0].device
         self.plan = torch.empty(max(_lib.quasar_sequence_plan_bytes(len(linears)), 16), dtype=torch.uint8, device=dev)
-        self.workspace = torch.empty(_lib.quasar_sequence_workspace_bytes(M), dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(_lib.quasar_sequence_workspace_bytes(len(linears), M), dtype=torch.uint8,
+                                     device=dev)
         self.handle = SequenceHandle()
         _check("quasar_sequence_prepare",
                _lib.quasar_sequence_prepare(ctypes.cast(descs, ctypes.c_void_p), len(linears),
                                             None if vdesc is None else ctypes.cast(ctypes.pointer(vdesc), ctypes.c_void_p),
                                             M, _ptr(self.plan), self.plan.numel(),
+                                            _ptr(self.workspace), self.workspace.numel(),
                                             ctypes.cast(ctypes.pointer(self.handle), ctypes.c_void_p)))
 
     @property
@@ -327,8 +329,8 @@ class Sequence:
         return self.handle.words[12]
 
     @property
-    def n_data_waits(self) -> int:
-        """Phases that wait for their input by polling the data itself (write-once buffers)."""
+    def n_flag_waits(self) -> int:
+        """Phases gated by the completion flags of their producer phases (write-once buffers)."""
         return self.handle.words[13]
 
     def run(self) -> None:

@@ -404,8 +404,8 @@ constexpr int kSeqMagic = 0x51534551;   // "QSEQ"
 constexpr unsigned int kSeqSpinLimit = 4000000u;
 
 struct SeqHandle {   // lives in quasar_sequence::words
-    int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears, arm_blocks;
-    int n_barriers, n_data_waits;
+    int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears, pad;
+    int n_barriers, n_flag_waits;
 };
 static_assert(sizeof(SeqHandle) <= sizeof(quasar_sequence), "handle must fit");
 
@@ -428,7 +428,7 @@ template <int MP, bool W16>
 int launch_sequence(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
     auto kernel = stream_sequence_kernel<MP, W16, kSeqWaves, kSeqDepth>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return QUASAR_ERR_HIP;
-    hipLaunchKernelGGL(sequence_arm_kernel, dim3(h.arm_blocks), dim3(256), 0, st, sp.phases, sp.nphases, sp.M, sp.sync);
+    hipLaunchKernelGGL(sequence_reset_kernel, dim3(1), dim3(64), 0, st, sp.sync);
     // Plain launch: one workgroup per compute unit is resident by construction (grid = number
     // of compute units, one workgroup fits each); a cooperative launch would add ~20 us.
     hipLaunchKernelGGL(kernel, dim3(h.grid), dim3(kSeqWaves * 64), (unsigned int)h.lds_bytes, st, sp);
@@ -444,14 +444,20 @@ size_t quasar_sequence_plan_bytes(int64_t n_linears) {
     return (size_t)(n_linears + 1) * sizeof(SeqPhase);
 }
 
-size_t quasar_sequence_workspace_bytes(int64_t M) {
-    if (M < 1 || M > 32) return 0;
-    return 256 + (size_t)kMaxGrid * 32u * sizeof(unsigned long long);
+// workspace: [256 B sync words][argmax partials][completion flags: (n_linears + 1) x grid]
+constexpr size_t kSeqPartialBytes = (size_t)kMaxGrid * 32u * sizeof(unsigned long long);
+
+size_t quasar_sequence_workspace_bytes(int64_t n_linears, int64_t M) {
+    if (M < 1 || M > 32 || n_linears < 0 || n_linears > (1 << 20)) return 0;
+    return 256 + kSeqPartialBytes + (size_t)(n_linears + 1) * kMaxGrid * sizeof(unsigned int);
 }
 
 int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears, const quasar_verify_desc *verify,
-                            int64_t M, void *plan_device, size_t plan_bytes, quasar_sequence *seq) {
-    if (!seq || !plan_device || (n_linears > 0 && !linears)) return QUASAR_ERR_NULL;
+                            int64_t M, void *plan_device, size_t plan_bytes, void *workspace, size_t workspace_bytes,
+                            quasar_sequence *seq) {
+    if (!seq || !plan_device || !workspace || (n_linears > 0 && !linears)) return QUASAR_ERR_NULL;
+    if (workspace_bytes < quasar_sequence_workspace_bytes(n_linears, M) || !aligned(workspace, 16))
+        return QUASAR_ERR_WORKSPACE;
     if (n_linears < 0 || (n_linears == 0 && !verify)) return QUASAR_ERR_SHAPE;
     if (M < 1 || M > 32) return QUASAR_ERR_SHAPE;
     if (plan_bytes < quasar_sequence_plan_bytes(n_linears)) return QUASAR_ERR_WORKSPACE;
@@ -467,14 +473,12 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
     struct Out { Range r; int ph, seg; long long N, ldy; const uint16_t *y; int writes; };
     std::vector<Out> outs;
     std::vector<Range> reads, writes;     // since the last device-wide barrier
-    // How does a phase reading `xr` (and writing `yrs`) have to wait?
-    //   - nothing it touches was touched since the last barrier            -> SEQ_WAIT_NONE
-    //   - its input is exactly one earlier output that is written only once in the whole
-    //     sequence, and its outputs clash with nothing                      -> SEQ_WAIT_DATA
-    //   - anything else (partial overlaps, reused buffers, write hazards)   -> SEQ_WAIT_BARRIER
-    auto classify = [&](const uint16_t *x, long long ldx, long long K, const Range &xr,
-                        const std::vector<Range> &yrs, int *producer) -> int {
-        *producer = -1;
+    // How does a phase reading `xr` (and writing `yrs`) have to wait?  (see SEQ_WAIT_* in
+    // stream_sequence.hpp)  Writes that clash with anything touched since the last barrier, or
+    // inputs in buffers written more than once, need the barrier; inputs that are write-once
+    // outputs of at most two earlier phases are gated by those phases' completion flags.
+    auto classify = [&](const Range &xr, const std::vector<Range> &yrs, int producers[2]) -> int {
+        producers[0] = producers[1] = -1;
         bool write_clash = false, raw = false;
         for (const Range &y : yrs) {
             for (const Range &wr : writes) if (overlaps(y, wr)) write_clash = true;
@@ -483,15 +487,16 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
         for (const Range &wr : writes) if (overlaps(xr, wr)) raw = true;
         if (write_clash) return SEQ_WAIT_BARRIER;
         if (!raw) return SEQ_WAIT_NONE;
-        int hits = 0, which = -1;
-        for (size_t i = 0; i < outs.size(); ++i)
-            if (overlaps(xr, outs[i].r)) { ++hits; which = (int)i; }
-        if (hits == 1 && outs[which].y == x && outs[which].ldy == ldx && outs[which].N == K &&
-            outs[which].writes == 1) {
-            *producer = which;
-            return SEQ_WAIT_DATA;
+        int n = 0;
+        for (const Out &o : outs) {
+            if (!overlaps(xr, o.r)) continue;
+            if (o.writes != 1) return SEQ_WAIT_BARRIER;
+            if (n > 0 && producers[0] == o.ph) continue;
+            if (n > 1 && producers[1] == o.ph) continue;
+            if (n == 2) return SEQ_WAIT_BARRIER;
+            producers[n++] = o.ph;
         }
-        return SEQ_WAIT_BARRIER;
+        return n > 0 ? SEQ_WAIT_FLAGS : SEQ_WAIT_BARRIER;
     };
     auto note_output = [&](const Range &yr, int ph, int seg, long long N, long long ldy, const uint16_t *y) {
         int n = 1;
@@ -522,7 +527,7 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
                 if (!clash) {
                     SeqSeg &sg = p.seg[p.nseg];
                     sg.w = static_cast<const u32x4 *>(d.w_packed); sg.scales = d.scales; sg.y = d.y; sg.ldy = d.ldy;
-                    sg.tile_begin = p.T; sg.N = (int)d.N; sg.arm = 0; sg.pad_ = 0;
+                    sg.tile_begin = p.T; sg.N = (int)d.N;
                     p.T += (int)(d.N / kTileRows);
                     note_output(yr, (int)phases.size() - 1, p.nseg, d.N, d.ldy, d.y);
                     ++p.nseg;
@@ -538,20 +543,19 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
         p.kind = EPI_LINEAR;
         p.seg[0].w = static_cast<const u32x4 *>(d.w_packed); p.seg[0].scales = d.scales; p.seg[0].y = d.y;
         p.seg[0].ldy = d.ldy; p.seg[0].tile_begin = 0; p.seg[0].N = (int)d.N;
-        int producer = -1;
-        p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(d.x, d.ldx, d.K, xr, {yr}, &producer);
+        p.producer[0] = p.producer[1] = -1;
+        p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(xr, {yr}, p.producer);
         if (p.wait == SEQ_WAIT_BARRIER) { reads.clear(); writes.clear(); }
-        if (p.wait == SEQ_WAIT_DATA) phases[outs[producer].ph].seg[outs[producer].seg].arm = 1;
         reads.push_back(xr);
         writes.push_back(yr);
         note_output(yr, (int)phases.size(), 0, d.N, d.ldy, d.y);
         phases.push_back(p);
     }
-    // an output that turned out to be written more than once must not be waited for by its data
+    // an output that turned out to be written again later must not be gated by flags
     for (SeqPhase &p : phases) {
-        if (p.wait != SEQ_WAIT_DATA) continue;
+        if (p.wait != SEQ_WAIT_FLAGS) continue;
         for (const Out &o : outs)
-            if (o.y == p.x && o.writes > 1) p.wait = SEQ_WAIT_BARRIER;
+            if ((o.ph == p.producer[0] || o.ph == p.producer[1]) && o.writes > 1) p.wait = SEQ_WAIT_BARRIER;
     }
     if (verify) {
         const quasar_verify_desc &v = *verify;
@@ -571,23 +575,15 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
         p.draft = v.draft_ids; p.n_draft = (int)v.n_draft; p.out_argmax = v.out_argmax; p.out_accept = v.out_accept_len;
         p.V = (int)v.V;
         const Range xr{reinterpret_cast<uintptr_t>(v.hidden), reinterpret_cast<uintptr_t>(v.hidden + (M - 1) * v.ldh + v.K)};
-        int producer = -1;
-        p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(v.hidden, v.ldh, v.K, xr, {}, &producer);
-        if (p.wait == SEQ_WAIT_DATA) {
-            if (outs[producer].writes > 1) p.wait = SEQ_WAIT_BARRIER;
-            else phases[outs[producer].ph].seg[outs[producer].seg].arm = 1;
-        }
+        p.producer[0] = p.producer[1] = -1;
+        p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(xr, {}, p.producer);
         phases.push_back(p);
     }
-    // a segment is armed only if every consumer that waits for its data is still in that mode
-    for (SeqPhase &p : phases)
-        for (int sgi = 0; sgi < p.nseg; ++sgi) {
-            if (!p.seg[sgi].arm) continue;
-            bool used = false;
-            for (const SeqPhase &c : phases)
-                if (c.wait == SEQ_WAIT_DATA && c.x == p.seg[sgi].y) used = true;
-            if (!used) p.seg[sgi].arm = 0;
-        }
+    for (SeqPhase &p : phases) {
+        if (p.wait != SEQ_WAIT_FLAGS) { p.producer[0] = p.producer[1] = -1; continue; }
+        phases[p.producer[0]].publish = 1;
+        if (p.producer[1] >= 0) phases[p.producer[1]].publish = 1;
+    }
 
     int xs_max = 0, sc_max = 0, acc_max = 0;
     for (SeqPhase &p : phases) {
@@ -601,15 +597,18 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
     if (lds > kMaxLds) return QUASAR_ERR_SHAPE;
     if (hipMemcpy(plan_device, phases.data(), phases.size() * sizeof(SeqPhase), hipMemcpyHostToDevice) != hipSuccess)
         return QUASAR_ERR_HIP;
+    // epoch and completion flags start from zero (the first launch runs in epoch 1)
+    if (hipMemset(workspace, 0, quasar_sequence_workspace_bytes(n_linears, M)) != hipSuccess) return QUASAR_ERR_HIP;
+    if (hipDeviceSynchronize() != hipSuccess) return QUASAR_ERR_HIP;
     SeqHandle h{};
     h.magic = kSeqMagic; h.nphases = (int)phases.size(); h.M = (int)M; h.MP = MP; h.w16 = w16 ? 1 : 0;
     h.xs_bytes = xs_max; h.sc_bytes = sc_max; h.lds_bytes = lds < kMinLds ? kMinLds : lds; h.grid = G;
     h.has_verify = verify ? 1 : 0; h.n_linears = (int)n_linears;
-    h.arm_blocks = 1;
-    for (const SeqPhase &p : phases)
-        for (int sgi = 0; sgi < p.nseg; ++sgi) if (p.seg[sgi].arm) h.arm_blocks = 128;
-    h.n_barriers = 0; h.n_data_waits = 0;
-    for (const SeqPhase &p : phases) { if (p.wait == SEQ_WAIT_BARRIER) ++h.n_barriers; if (p.wait == SEQ_WAIT_DATA) ++h.n_data_waits; }
+    h.n_barriers = 0; h.n_flag_waits = 0;
+    for (const SeqPhase &p : phases) {
+        if (p.wait == SEQ_WAIT_BARRIER) ++h.n_barriers;
+        if (p.wait == SEQ_WAIT_FLAGS) ++h.n_flag_waits;
+    }
     std::memset(seq, 0, sizeof(*seq));
     std::memcpy(seq, &h, sizeof(h));
     return QUASAR_OK;
@@ -621,7 +620,7 @@ int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, voi
     SeqHandle h;
     std::memcpy(&h, seq, sizeof(h));
     if (h.magic != kSeqMagic || h.nphases < 1) return QUASAR_ERR_SHAPE;
-    if (workspace_bytes < quasar_sequence_workspace_bytes(h.M)) return QUASAR_ERR_WORKSPACE;
+    if (workspace_bytes < quasar_sequence_workspace_bytes(h.n_linears, h.M)) return QUASAR_ERR_WORKSPACE;
     if (!aligned(workspace, 16) || !aligned(plan_device, 16)) return QUASAR_ERR_ALIGN;
     if (h.grid != device_cus()) return QUASAR_ERR_SHAPE;     // prepared for another device
     SeqParams sp{};
@@ -629,6 +628,7 @@ int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, voi
     sp.nphases = h.nphases; sp.M = h.M; sp.xs_bytes = h.xs_bytes; sp.sc_bytes = h.sc_bytes;
     sp.sync = static_cast<unsigned int *>(workspace);
     sp.partial = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(workspace) + 256);
+    sp.flags = reinterpret_cast<unsigned int *>(static_cast<unsigned char *>(workspace) + 256 + kSeqPartialBytes);
     sp.spin_limit = kSeqSpinLimit;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (h.w16) {

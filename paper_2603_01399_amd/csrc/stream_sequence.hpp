@@ -24,11 +24,13 @@ namespace quasar {
 
 constexpr int kMaxSeg = 4;
 
-enum { SEQ_WAIT_NONE = 0, SEQ_WAIT_BARRIER = 1, SEQ_WAIT_DATA = 2 };
-
-// bf16 bit pattern that the epilogue never produces (NaN results are canonicalised to 0x7FC0):
-// marks "not written yet" in activation buffers that are handed from phase to phase
-constexpr unsigned int kNotYet16 = 0xFFFFu;
+// How the input of a phase becomes available:
+//   NONE     it was there before the launch;
+//   FLAGS    it is the write-once output of one or two earlier phases: every workgroup raises a
+//            per-phase flag when its share of such a phase is stored, the consumer polls the
+//            flags of all workgroups and then reads the data through the caches;
+//   BARRIER  anything else (buffers written more than once, write hazards): device-wide barrier.
+enum { SEQ_WAIT_NONE = 0, SEQ_WAIT_BARRIER = 1, SEQ_WAIT_FLAGS = 2 };
 
 struct SeqSeg {
     const u32x4 *w;          // packed weights of this member matrix
@@ -37,8 +39,6 @@ struct SeqSeg {
     long long ldy;
     int tile_begin;          // index of the segment's first tile inside the phase
     int N;
-    int arm;                 // y is consumed through SEQ_WAIT_DATA: pre-filled with kNotYet16
-    int pad_;
 };
 
 struct SeqPhase {
@@ -55,6 +55,9 @@ struct SeqPhase {
     int32_t *out_accept;
     int n_draft;
     int V;
+    int producer[2];         // SEQ_WAIT_FLAGS: phases whose completion flags gate this input (-1: unused)
+    int publish;             // a later phase waits for this phase's flags
+    int pad_;
 };
 
 typedef const __attribute__((address_space(4))) SeqPhase *const_phase_ptr;   // scalar (constant) loads
@@ -72,7 +75,8 @@ struct SeqParams {
     int M;
     int xs_bytes;            // LDS reserved for activations (max over phases)
     int sc_bytes;            // LDS reserved for row scales (max over phases)
-    unsigned int *sync;      // [0] arrival counter (zero at launch), [1] error flag (zero at launch)
+    unsigned int *sync;      // [0] arrival counter, [1] error flag (both zero at launch), [2] launch epoch
+    unsigned int *flags;     // [nphases][gridDim.x]: epoch of the launch in which the workgroup finished the phase
     unsigned long long *partial;   // argmax phase: [gridDim.x][MP] packed (logit, index) keys
     unsigned int spin_limit; // bound on polling iterations
 };
@@ -94,14 +98,6 @@ __device__ __forceinline__ u32x4 coherent_load_u32x4(const void *p) {
     const unsigned long long hi = coherent_load_u64(static_cast<const unsigned long long *>(p) + 1);
     return u32x4{(unsigned int)lo, (unsigned int)(lo >> 32), (unsigned int)hi, (unsigned int)(hi >> 32)};
 }
-__device__ __forceinline__ bool has_not_yet(const u32x4 &v) {
-    bool r = false;
-    const unsigned int wd[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) r = r || (wd[i] & 0xFFFFu) == kNotYet16 || (wd[i] >> 16) == kNotYet16;
-    return r;
-}
-
 // All workgroups of the launch meet.  Every wave first waits until its own (coherent) stores
 // have been acknowledged, so whatever the workgroup wrote is readable device-wide once the
 // arrival counter has been bumped.  Polling is bounded: on timeout the error flag is raised
@@ -141,7 +137,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     constexpr int PPS = W16 ? 4 : 8;
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
     constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
-    constexpr int XB = 4;
+    constexpr int XB = 8;
     constexpr int nthreads = NW * 64;
     static_assert(NW == 16, "the in-kernel second stage of the verify phase assumes 1024 threads");
 
@@ -158,6 +154,12 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     uint16_t *sc_lds = reinterpret_cast<uint16_t *>(lds + sp.xs_bytes);
     f32x4 *stage = reinterpret_cast<f32x4 *>(lds + sp.xs_bytes + sp.sc_bytes);   // [2][NW][NB][64]
     f32x4 *accs = stage + 2 * NW * NB * 64;                                      // [ntiles][NB][64] (C > 1)
+
+    // Activations produced inside the launch are later read through the caches.  Lines of an
+    // earlier launch (same addresses, old values) cannot be hit: the packet processor
+    // invalidates the caches when a kernel starts (an explicit invalidate here costs ~25 us).
+    const unsigned int epoch = __builtin_amdgcn_readfirstlane(
+        __hip_atomic_load(as_global(&sp.sync[2]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 
     auto seg_of = [&](const auto &P, int t) -> int {
         int s = 0;
@@ -256,40 +258,46 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     }
     const int xm = (MP == 8) ? (mcol & 7) : mcol;
 
-    // stage one activation chunk; with SEQ_WAIT_DATA the loads are repeated until no element
-    // carries the "not written yet" pattern any more
-    auto x_stage = [&](const auto &P, int c, bool poll) {
+    // stage one activation chunk.  `coherent` reads go past the L2 (needed when the buffer may
+    // have been cached before it was last written: barrier-ordered, reused buffers); otherwise
+    // the 32 compute units of an XCD share one fetch of the activations through their L2.
+    auto x_stage = [&](const auto &P, int c, bool coherent) {
         const int scc = min(P.SC, P.S - c * P.SC);
         const int npieces = scc * PPS * MP;
         for (int base = 0; base < npieces; base += nthreads * XB) {
             u32x4 v[XB];
-            unsigned int spins = 0;
-            for (;;) {
-                bool again = false;
 #pragma unroll
-                for (int i = 0; i < XB; ++i) {
-                    const int idx = base + i * nthreads + tid;
-                    v[i] = u32x4{0u, 0u, 0u, 0u};
-                    if (idx < npieces) {
-                        const int m = idx & (MP - 1), p8 = idx >> LMP;
-                        if (m < M) {
-                            const long long k = (long long)c * P.SC * KSTEP + 8ll * p8;
-                            v[i] = coherent_load_u32x4(P.x + m * P.ldx + k);
-                            again = again || (poll && has_not_yet(v[i]));
-                        }
+            for (int i = 0; i < XB; ++i) {
+                const int idx = base + i * nthreads + tid;
+                v[i] = u32x4{0u, 0u, 0u, 0u};
+                if (idx < npieces) {
+                    const int m = idx & (MP - 1), p8 = idx >> LMP;
+                    if (m < M) {
+                        const long long k = (long long)c * P.SC * KSTEP + 8ll * p8;
+                        if (coherent) v[i] = coherent_load_u32x4(P.x + m * P.ldx + k);
+                        else v[i] = *as_global(reinterpret_cast<const u32x4 *>(P.x + m * P.ldx + k));
                     }
-                }
-                if (!again) break;
-                if (++spins > sp.spin_limit ||
-                    __hip_atomic_load(as_global(&sp.sync[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
-                    __hip_atomic_store(as_global(&sp.sync[1]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
                 }
             }
 #pragma unroll
             for (int i = 0; i < XB; ++i) {
                 const int idx = base + i * nthreads + tid;
                 if (idx < npieces) xs[idx] = v[i];
+            }
+        }
+    };
+    // wait until every workgroup has raised its flag for phase `pp` in this launch
+    auto flags_wait = [&](int pp) {
+        for (int t = tid; t < G; t += nthreads) {
+            unsigned int spins = 0;
+            while (__hip_atomic_load(as_global(sp.flags + (long long)pp * G + t), __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+                if (++spins > sp.spin_limit ||
+                    __hip_atomic_load(as_global(&sp.sync[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                    __hip_atomic_store(as_global(&sp.sync[1]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
             }
         }
     };
@@ -307,6 +315,14 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     // end of a phase: publish argmax partials and run the second stage
     auto phase_end = [&](int ph) {
         const auto &P = phases[ph];
+        if (P.publish) {
+            // every wave's output stores have been acknowledged before the flag goes up
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            lds_barrier();
+            if (tid == 0)
+                __hip_atomic_store(as_global(sp.flags + (long long)ph * G + b), epoch, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
         if (P.kind != EPI_ARGMAX) return;
         unsigned long long *red = reinterpret_cast<unsigned long long *>(stage);   // [NW][MP]
         lds_barrier();
@@ -389,7 +405,11 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     ++barriers_done;
                     grid_barrier(sp.sync, barriers_done * (unsigned int)G, sp.spin_limit);
                 } else {
-                    lds_barrier();   // the previous phase's last epilogue has read its scales
+                    if (P.wait == SEQ_WAIT_FLAGS) {
+                        flags_wait(P.producer[0]);
+                        if (P.producer[1] >= 0) flags_wait(P.producer[1]);
+                    }
+                    lds_barrier();   // flags seen by all; the previous phase's last epilogue has read its scales
                 }
                 if (c_ntiles == 0) { c_c = c_C - 1; continue; }   // nothing to do here but the waits
                 scale_stage(P, c_t0, c_ntiles);
@@ -402,7 +422,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             c_si = 0;
             c_reseg();
             QUASAR_TRACE(1)
-            x_stage(P, c_c, P.wait == SEQ_WAIT_DATA);
+            x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
             QUASAR_TRACE(2)
             // known-empty load queue: keeps the counted waits of the ring exact (see stream_gemm.hpp)
             __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -526,24 +546,14 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     }
 }
 
-// Clears the two sync words ahead of a sequence launch and pre-fills the activation buffers
-// that are handed from phase to phase with the "not written yet" pattern (kernels rather
-// than memsets so that callers may capture the call sequence in a graph).
-__global__ __launch_bounds__(256) void sequence_arm_kernel(const SeqPhase *phases, int nphases, int M,
-                                                           unsigned int *sync) {
-    if (blockIdx.x == 0 && threadIdx.x < 2) sync[threadIdx.x] = 0u;
-    for (int ph = 0; ph < nphases; ++ph) {
-        const SeqPhase &P = phases[ph];
-        for (int s = 0; s < P.nseg; ++s) {
-            if (!P.seg[s].arm) continue;
-            const long long n4 = (long long)P.seg[s].N / 4;         // 8-byte units per row
-            const long long total = n4 * M;
-            for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total;
-                 i += (long long)gridDim.x * 256) {
-                const long long m = i / n4, j = i - m * n4;
-                *reinterpret_cast<unsigned long long *>(P.seg[s].y + m * P.seg[s].ldy + 4 * j) = ~0ull;
-            }
-        }
+// Runs ahead of every sequence launch: clears the barrier counter and the error flag and
+// starts a new epoch for the completion flags (a kernel rather than a memset so that callers
+// may capture the call sequence in a graph).
+__global__ void sequence_reset_kernel(unsigned int *sync) {
+    if (threadIdx.x == 0) {
+        sync[0] = 0u;
+        sync[1] = 0u;
+        sync[2] = sync[2] + 1u;
     }
 }
 

@@ -124,7 +124,7 @@ def test_sequence_chain_vs_oracle_and_single_calls(qb, M, hidden, kv, inter, bf1
                               out_argmax, out_accept))
     assert seq.nphases == 4 * n_layers + 1          # q|k|v, o, gate|up, down per layer + the head
     # every buffer is written once: all dependent phases wait for their data, none at a barrier
-    assert seq.n_barriers == 0 and seq.n_data_waits == 4 * n_layers
+    assert seq.n_barriers == 0 and seq.n_flag_waits == 4 * n_layers
     seq.run()
     torch.cuda.synchronize()
     assert not seq.timed_out()
@@ -167,6 +167,29 @@ def test_sequence_chain_vs_oracle_and_single_calls(qb, M, hidden, kv, inter, bf1
     assert not seq.timed_out()
     for li in range(n_layers):
         assert torch.equal(first[li].view(torch.int16), bufs[li]["down"].view(torch.int16))
+
+
+def test_sequence_rerun_with_new_input_sees_fresh_activations(qb):
+    """The same prepared sequence is run again after its input (same address) was overwritten:
+    every intermediate buffer is produced again and must be read fresh, not from a cache line
+    that still holds the previous step's value."""
+    print("sequence rerun", flush=True)
+    M, hidden, kv, inter, n_layers = 8, 256, 64, 768, 3
+    layers = build_model(qb, n_layers, hidden, kv, inter, seed=9800)
+    x_a = synth.activations_bf16(M, hidden, seed=9801)
+    x_b = synth.activations_bf16(M, hidden, seed=9802)
+    bufs, h_dev = gpu_buffers(layers, M, x_a)
+    seq = qb.Sequence(linear_list(layers, bufs))
+    for xb in (x_a, x_b, x_a, x_b):
+        bufs[0]["in"].copy_(bf16_to_dev(xb))
+        seq.run()
+        torch.cuda.synchronize()
+        assert not seq.timed_out()
+        want, _ = oracle_chain(layers, xb)
+        for li in range(n_layers):
+            for name in ("q", "o", "up", "down"):
+                got = ref.bf16_bits_to_f64(bf16_to_host(bufs[li][name]))
+                assert ref.rel_maxabs_err(got, want[li][name][0]) <= TOL, (li, name)
 
 
 def test_sequence_reused_buffers_fall_back_to_barriers(qb):
