@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--detail", action="store_true", help="also time every linear shape cold, the bf16 twin step "
                     "and the pure read stream (stderr)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true", help="also run the plain copy kernel over 1 GiB (reference "
+                    "for scaling hardware byte counters in rocprofv3 --pmc runs)")
     ap.add_argument("--no-twin", action="store_true", help="skip the bf16-weight twin of the step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -149,6 +151,14 @@ def main() -> int:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / steps      # us per step
 
+    if args.calibrate:
+        src = torch.empty(1 << 30, dtype=torch.int8, device=dev).random_(-128, 127)
+        dst = torch.empty(1 << 30, dtype=torch.int8, device=dev)
+        for _ in range(3):
+            qb.copy_stream(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
     calls8 = plan(True)
 
     def make_sequence(calls):
@@ -197,7 +207,7 @@ def main() -> int:
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("w8_linear_bytes_per_launch")
+            traffic = json.load(open(tpath)).get("sequence_step_bytes_per_launch")
         except Exception:
             traffic = None
 
@@ -235,6 +245,30 @@ def main() -> int:
             log(f"  cold {name:10s} {K:6d}->{N:6d}: {us:7.2f} us  {lin_bytes(K, N, 1) / us / 1e3:7.1f} GB/s "
                 f"({lin_bytes(K, N, 1) / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
             detail[f"cold_{name}_us"] = us
+        # VALU dot-product path against the MFMA path at small M (the measured crossover)
+        gi = [i for i, sh in enumerate(shapes) if sh[0] == "gate_proj"][0]
+        _, Kg, Ng = shapes[gi]
+        for Mv in (1, 2, 4):
+            xv = torch.randn((Mv, Kg), device=dev).to(torch.bfloat16)
+            yv = torch.empty((Mv, Ng), dtype=torch.bfloat16, device=dev)
+            for pname, pid in (("valu", qb.PATH_VALU), ("mfma", qb.PATH_MFMA)):
+                qb.set_path(pid)
+                def gov():
+                    for lin in layers:
+                        qb.w8_linear(xv, lin[gi][3], lin[gi][4], Ng, yv)
+                gov()
+                torch.cuda.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(3):
+                    gov()
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / (3 * L)
+                log(f"  cold gate_proj M={Mv} path={pname}: {us:7.2f} us  {Ng * Kg / us / 1e3:7.1f} GB/s")
+                detail[f"gate_proj_M{Mv}_{pname}_us"] = us
+            qb.set_path(qb.PATH_AUTO)
         sink = torch.zeros(4096, dtype=torch.int32, device=dev)
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
