@@ -203,6 +203,22 @@ def main() -> int:
     achieved = step_bytes[1] / us_step / 1e3
     avg_b, avg_us = float(step_bytes[1]), us_step
 
+    # The same weights with every linear reading a resident input instead of its predecessor's
+    # output (no phase waits for another): what the weight stream alone sustains.
+    fixed_in = {4096: h0, 12288: torch.randn((M, 12288), generator=gen, device=dev, dtype=torch.float32)
+                .to(torch.bfloat16)}
+    lin_free = []
+    for li, lin in enumerate(layers):
+        for name, K, N, wq, sc, wp in lin:
+            lin_free.append((fixed_in[K], wq, sc, N, bufs[li][{"q_proj": "q", "k_proj": "k", "v_proj": "v",
+                                                               "o_proj": "o", "gate_proj": "g", "up_proj": "u",
+                                                               "down_proj": "d"}[name]]))
+    seq_free = qb.Sequence(lin_free, verify=(h0, head_q, head_s, V, draft, out_argmax, out_accept))
+    us_free = time_sequence(seq_free, max(2, args.steps // 2), 2)
+    log(f"int8 step with independent inputs ({seq_free.nphases} phases, {seq_free.n_flag_waits} flag waits): "
+        f"{us_free:.1f} us -> {step_bytes[1] / us_free / 1e3:.1f} GB/s")
+    del seq_free
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -211,7 +227,8 @@ def main() -> int:
         except Exception:
             traffic = None
 
-    detail = {}
+    detail = {"independent_inputs_us_per_step": us_free,
+              "independent_inputs_hbm_gbps": step_bytes[1] / us_free / 1e3}
     us_twin = None
     if twin:
         seq16 = make_sequence(plan(False))

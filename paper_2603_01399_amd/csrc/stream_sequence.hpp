@@ -126,8 +126,15 @@ __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int ta
     if ((b == 0 || b == 100) && tid == 0 && c_ph < 400)                                              \
         reinterpret_cast<unsigned long long *>(sp.partial)[65536 + ((b ? 1 : 0) * 400 + c_ph) * 8 + (slot)] = \
             __builtin_readcyclecounter();
+#define QUASAR_TRACE_SLOT(tag)                                                                      \
+    if (b == 0 && tid == 0 && trace_n < 2000) {                                                     \
+        reinterpret_cast<unsigned long long *>(sp.partial)[80000 + trace_n] =                       \
+            ((unsigned long long)(tag) << 56) | (__builtin_readcyclecounter() & 0x00FFFFFFFFFFFFFFull); \
+        ++trace_n;                                                                                  \
+    }
 #else
 #define QUASAR_TRACE(slot)
+#define QUASAR_TRACE_SLOT(tag)
 #endif
 
 template <int MP, bool W16, int NW, int D>
@@ -438,6 +445,9 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     // exit from the round, or re-entering it through a switch - makes the compiler lose count of
     // the outstanding ring loads and drain the ring.  After the last phase the rest of the
     // round consumes empty slots.
+#ifdef QUASAR_SEQ_TRACE
+    int trace_n = 0;
+#endif
     bool running = true;
     while (running) {
 #pragma unroll
@@ -451,6 +461,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     c_nsl = 0x7FFFFFFF;
                 }
             }
+            QUASAR_TRACE_SLOT(1)
             const bool valid = c_si < c_spw;
             u32x4 wv = ring[d];
             if (!valid) wv = u32x4{0u, 0u, 0u, 0u};
@@ -458,8 +469,10 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             if constexpr (!W16) {
                 const bf16x8 a0 = codes_to_bf16x8(wv.x, wv.y);
                 const bf16x8 a1 = codes_to_bf16x8(wv.z, wv.w);
+                QUASAR_TRACE_SLOT(2)
                 ring[d] = ring_refill(l_addr(), wv);
                 l_advance();
+                QUASAR_TRACE_SLOT(3)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     const u32x4 b0 = xs[(piece0 + 2 * g) * MP + xm + 16 * nb];
@@ -480,6 +493,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 ring[d] = ring_refill(l_addr(), wv);
                 l_advance();
             }
+            QUASAR_TRACE_SLOT(4)
             if (c_si == c_nsl - 1) {
                 // ---- tile end: cross-wave sum through LDS, fixed order
                 f32x4 *st = stage + (parity * NW) * NB * 64;
@@ -535,6 +549,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     }
                 }
                 parity ^= 1;
+                QUASAR_TRACE_SLOT(5)
             }
             // advance the compute front
             if (++c_si >= c_nsl) {
