@@ -439,9 +439,11 @@ int launch_sequence(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
 
 extern "C" {
 
+constexpr size_t kSeqZeroBytes = 1024;
+
 size_t quasar_sequence_plan_bytes(int64_t n_linears) {
     if (n_linears < 0 || n_linears > (1 << 20)) return 0;
-    return (size_t)(n_linears + 1) * sizeof(SeqPhase);
+    return (size_t)(n_linears + 1) * sizeof(SeqPhase) + kSeqZeroBytes;   // phase table, block of zeros
 }
 
 // workspace: [256 B sync words][argmax partials][completion flags: (n_linears + 1) x grid]
@@ -597,6 +599,9 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
     if (lds > kMaxLds) return QUASAR_ERR_SHAPE;
     if (hipMemcpy(plan_device, phases.data(), phases.size() * sizeof(SeqPhase), hipMemcpyHostToDevice) != hipSuccess)
         return QUASAR_ERR_HIP;
+    if (hipMemset(static_cast<unsigned char *>(plan_device) + (size_t)(n_linears + 1) * sizeof(SeqPhase), 0,
+                  kSeqZeroBytes) != hipSuccess)
+        return QUASAR_ERR_HIP;
     // epoch and completion flags start from zero (the first launch runs in epoch 1)
     if (hipMemset(workspace, 0, quasar_sequence_workspace_bytes(n_linears, M)) != hipSuccess) return QUASAR_ERR_HIP;
     if (hipDeviceSynchronize() != hipSuccess) return QUASAR_ERR_HIP;
@@ -630,6 +635,8 @@ int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, voi
     sp.partial = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(workspace) + 256);
     sp.flags = reinterpret_cast<unsigned int *>(static_cast<unsigned char *>(workspace) + 256 + kSeqPartialBytes);
     sp.spin_limit = kSeqSpinLimit;
+    sp.zeros = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(plan_device) +
+                                               (size_t)(h.n_linears + 1) * sizeof(SeqPhase));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (h.w16) {
         if (h.MP == 8) return launch_sequence<8, true>(h, sp, st);

@@ -58,6 +58,13 @@ __device__ __forceinline__ u32x4 ring_refill(const u32x4 *addr, const u32x4 &use
     return __builtin_nontemporal_load(reinterpret_cast<global_u32x4_ptr>(a));
 }
 
+// The same with a wave-uniform base address (kept in scalar registers) and a per-lane byte
+// offset; the tie goes through the offset register.
+__device__ __forceinline__ u32x4 ring_refill_at(unsigned long long base, unsigned int &lane_offset, const u32x4 &used) {
+    asm volatile("" : "+v"(lane_offset) : "v"(used.x), "v"(used.y), "v"(used.z), "v"(used.w));
+    return __builtin_nontemporal_load(reinterpret_cast<global_u32x4_ptr>(base + lane_offset));
+}
+
 template <int NW, int D>
 struct WaveWalk {
     const GemmParams &p;

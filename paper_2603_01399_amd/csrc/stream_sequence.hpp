@@ -79,6 +79,7 @@ struct SeqParams {
     unsigned int *flags;     // [nphases][gridDim.x]: epoch of the launch in which the workgroup finished the phase
     unsigned long long *partial;   // argmax phase: [gridDim.x][MP] packed (logit, index) keys
     unsigned int spin_limit; // bound on polling iterations
+    const u32x4 *zeros;      // 1 KB of zeros, never written: what a slot without a weight step loads
 };
 
 // Data that crosses from one phase to a later one inside the launch (outputs read as the
@@ -125,7 +126,12 @@ __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int ta
 #define QUASAR_TRACE(slot)                                                                          \
     if ((b == 0 || b == 100) && tid == 0 && c_ph < 400)                                              \
         reinterpret_cast<unsigned long long *>(sp.partial)[65536 + ((b ? 1 : 0) * 400 + c_ph) * 8 + (slot)] = \
-            __builtin_readcyclecounter();
+            __builtin_readcyclecounter();                                                           \
+    if (tid == 0 && c_ph < 60 && b < 256 && ((slot) == 0 || (slot) == 4 || (slot) == 5))            \
+        reinterpret_cast<unsigned long long *>(sp.partial)[84000 + (c_ph * 256 + b) * 3 + ((slot) == 0 ? 0 : (slot) - 3)] = \
+            (__builtin_amdgcn_s_memrealtime() & 0x0000FFFFFFFFFFFFull) |                            \
+            ((unsigned long long)__builtin_amdgcn_s_getreg(6164) << 60) |                           \
+            ((unsigned long long)(__builtin_amdgcn_s_getreg(63492) & 0xFFFF) << 44);
 #define QUASAR_TRACE_SLOT(tag)                                                                      \
     if (b == 0 && tid == 0 && trace_n < 2000) {                                                     \
         reinterpret_cast<unsigned long long *>(sp.partial)[80000 + trace_n] =                       \
@@ -177,26 +183,33 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     };
 
     // ------------------------------------------------------------------ load front
-    // everything the per-slot path needs lives in registers; the phase table is read only
-    // when the front enters a new (phase, chunk) or crosses into another member matrix
-    int l_ph = 0, l_c = -1, l_tl = 0, l_si = 0, l_nsl = 1, l_spw = 0, l_ntiles = 0, l_t0 = 0, l_seg_end = 0;
-    int l_s_lo = 0;
-    long long l_stride = 0;
-    const u32x4 *l_wt = nullptr;
+    // A run is this wave's consecutive steps inside one tile: the per-slot path only bumps a
+    // scalar address and counts the run down; the phase table is read when a run ends.  Runs
+    // without a step (this wave has no share of the K chunk, or the sequence is over) read a
+    // block of zeros, so such a slot contributes nothing without any masking.
+    constexpr int kForever = 0x7FFFFFFF;
+    const unsigned long long zeros = reinterpret_cast<unsigned long long>(sp.zeros);
+    int l_ph = 0, l_c = -1, l_tl = 0, l_spw = 0, l_ntiles = 0, l_t0 = 0, l_seg_end = 0, l_s_lo = 0;
+    unsigned long long l_stride = 0;   // bytes from one tile to the next
+    unsigned long long l_wt = 0;       // this wave's first step in the current tile
+    unsigned long long l_base = zeros; // the next slot to load
+    unsigned int l_inc = 0;
+    int l_left = 1;
     auto l_retile = [&]() {
         const auto &P = phases[l_ph];
         const int t = l_t0 + l_tl;
         const int s = seg_of(P, t);
         l_seg_end = (s + 1 < P.nseg) ? P.seg[s + 1].tile_begin : P.T;
-        l_stride = (long long)P.S * 64;
-        l_wt = P.seg[s].w + ((long long)(t - P.seg[s].tile_begin) * P.S + (long long)l_c * P.SC + l_s_lo) * 64;
+        l_stride = (unsigned long long)P.S * 1024ull;
+        l_wt = reinterpret_cast<unsigned long long>(P.seg[s].w) +
+               ((unsigned long long)(t - P.seg[s].tile_begin) * P.S + (unsigned long long)l_c * P.SC + l_s_lo) * 1024ull;
     };
     // move to the next (phase, chunk) in which this workgroup has tiles
     auto l_next = [&]() {
         for (;;) {
             ++l_c;
             if (l_ph < nph && l_c >= phases[l_ph].C) { ++l_ph; l_c = 0; }
-            if (l_ph >= nph) { l_ntiles = 0; l_spw = 0; l_nsl = 1; return; }
+            if (l_ph >= nph) { l_ntiles = 0; l_spw = 0; return; }
             const auto &P = phases[l_ph];
             l_t0 = (int)(((long long)P.T * b) / G);
             l_ntiles = (int)(((long long)P.T * (b + 1)) / G) - l_t0;
@@ -204,40 +217,43 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             const int scc = min(P.SC, P.S - l_c * P.SC);
             l_s_lo = (scc * w) / NW;
             l_spw = (scc * (w + 1)) / NW - l_s_lo;
-            l_nsl = max(l_spw, 1);
             l_tl = 0;
-            l_si = 0;
             l_retile();
             return;
         }
     };
-    auto l_advance = [&]() {
-        if (l_ph >= nph) return;
-        if (++l_si < l_nsl) return;
-        l_si = 0;
-        if (++l_tl < l_ntiles) {
-            if (l_t0 + l_tl == l_seg_end) l_retile(); else l_wt += l_stride;
-            return;
-        }
-        l_next();
+    auto l_run = [&]() {
+        if (l_ph < nph && l_spw > 0) { l_base = l_wt; l_inc = 1024u; l_left = l_spw; }
+        else { l_base = zeros; l_inc = 0u; l_left = l_ph < nph ? 1 : kForever; }
     };
-    auto l_addr = [&]() -> const u32x4 * {
-        const bool real = l_ph < nph && l_si < l_spw;
-        // slots without a step read one hot, read-only line (never the line of the barrier words)
-        return real ? l_wt + (long long)l_si * 64 + lane : reinterpret_cast<const u32x4 *>(sp.phases);
+    auto l_event = [&]() {
+        if (l_ph < nph) {
+            if (++l_tl < l_ntiles) {
+                if (l_t0 + l_tl == l_seg_end) l_retile(); else l_wt += l_stride;
+            } else {
+                l_next();
+            }
+        }
+        l_run();
     };
 
+    unsigned int voff = (unsigned int)lane * 16u;
     l_next();
+    l_run();
     u32x4 ring[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-        ring[d] = ring_refill(l_addr(), u32x4{0u, 0u, 0u, 0u});
-        l_advance();
+        ring[d] = ring_refill_at(l_base, voff, u32x4{0u, 0u, 0u, 0u});
+        l_base += l_inc;
+        if (--l_left == 0) l_event();
     }
 
     // ------------------------------------------------------------------ compute front
-    int c_ph = 0, c_c = -1, c_tl = 0, c_si = 0, c_nsl = 1, c_spw = 0, c_ntiles = 0, c_t0 = 0, c_s_lo = 0;
+    int c_ph = 0, c_c = -1, c_tl = 0, c_nsl = 1, c_ntiles = 0, c_t0 = 0;
     int c_C = 1, c_kind = EPI_LINEAR;
+    int c_left = kForever;             // slots to the end of the current tile
+    unsigned int c_x0 = 0, c_xinc = 0; // LDS offset of this wave's first step in the chunk; bytes per step
+    unsigned int c_xoff = 0;           // LDS offset of the current slot's activations
     // output segment of the current tile, kept in registers so that the tile-end path reads
     // nothing from the phase table
     uint16_t *c_y = nullptr;
@@ -251,7 +267,6 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
         c_tb = P.seg[s].tile_begin;
         c_seg_end = (s + 1 < P.nseg) ? P.seg[s + 1].tile_begin : P.T;
     };
-    bool need_enter = true;
     unsigned int barriers_done = 0;
     int parity = 0;
     f32x4 acc[NB];
@@ -264,6 +279,8 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
         besti[nb] = 0x7FFFFFFFu;
     }
     const int xm = (MP == 8) ? (mcol & 7) : mcol;
+    // this lane's B operand inside a step: 8-element piece (W16: g, else 2g and 2g + 1), token xm
+    const unsigned int xlane = (unsigned int)(((W16 ? g : 2 * g) * MP + xm) * 16);
 
     // stage one activation chunk.  `coherent` reads go past the L2 (needed when the buffer may
     // have been cached before it was last written: barrier-ordered, reused buffers); otherwise
@@ -422,11 +439,12 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 scale_stage(P, c_t0, c_ntiles);
             }
             const int scc = min(P.SC, P.S - c_c * P.SC);
-            c_s_lo = (scc * w) / NW;
-            c_spw = (scc * (w + 1)) / NW - c_s_lo;
-            c_nsl = max(c_spw, 1);
+            const int s_lo = (scc * w) / NW;
+            const int spw = (scc * (w + 1)) / NW - s_lo;
+            c_nsl = max(spw, 1);
+            c_xinc = spw > 0 ? (unsigned int)(PPS * MP * 16) : 0u;
+            c_x0 = spw > 0 ? (unsigned int)s_lo * (unsigned int)(PPS * MP * 16) : 0u;
             c_tl = 0;
-            c_si = 0;
             c_reseg();
             QUASAR_TRACE(1)
             x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
@@ -440,43 +458,37 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
         }
     };
 
-    // The rare phase/chunk entry code is inlined into every slot of the unrolled round (the
-    // build raises the compiler's pragma-unroll size limit for this): any other shape - a side
-    // exit from the round, or re-entering it through a switch - makes the compiler lose count of
-    // the outstanding ring loads and drain the ring.  After the last phase the rest of the
-    // round consumes empty slots.
+    // The rare paths (end of a run, end of a tile, entry into the next phase or chunk) are
+    // inlined into every slot of the unrolled round (the build raises the compiler's
+    // pragma-unroll size limit for this): any other shape - a side exit from the round, or
+    // re-entering it through a switch - makes the compiler lose count of the outstanding ring
+    // loads and drain the ring.  After the last phase the rest of the round consumes slots of
+    // zeros.
 #ifdef QUASAR_SEQ_TRACE
     int trace_n = 0;
 #endif
-    bool running = true;
+    const unsigned char *xsb = lds;
+    bool running = c_enter();
+    if (running) { c_left = c_nsl; c_xoff = c_x0; }
     while (running) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            if (__builtin_expect(need_enter, 0)) {
-                need_enter = false;
-                if (!c_enter()) {
-                    running = false;
-                    c_spw = 0;
-                    c_si = 0;
-                    c_nsl = 0x7FFFFFFF;
-                }
-            }
             QUASAR_TRACE_SLOT(1)
-            const bool valid = c_si < c_spw;
-            u32x4 wv = ring[d];
-            if (!valid) wv = u32x4{0u, 0u, 0u, 0u};
-            const int piece0 = (valid ? c_s_lo + c_si : 0) * PPS;
+            const u32x4 wv = ring[d];
+            const unsigned char *xp = xsb + (xlane + c_xoff);
+            c_xoff += c_xinc;
             if constexpr (!W16) {
                 const bf16x8 a0 = codes_to_bf16x8(wv.x, wv.y);
                 const bf16x8 a1 = codes_to_bf16x8(wv.z, wv.w);
                 QUASAR_TRACE_SLOT(2)
-                ring[d] = ring_refill(l_addr(), wv);
-                l_advance();
+                ring[d] = ring_refill_at(l_base, voff, wv);
+                l_base += l_inc;
+                if (__builtin_expect(--l_left == 0, 0)) l_event();
                 QUASAR_TRACE_SLOT(3)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const u32x4 b0 = xs[(piece0 + 2 * g) * MP + xm + 16 * nb];
-                    const u32x4 b1 = xs[(piece0 + 2 * g + 1) * MP + xm + 16 * nb];
+                    const u32x4 b0 = *reinterpret_cast<const u32x4 *>(xp + nb * 256);
+                    const u32x4 b1 = *reinterpret_cast<const u32x4 *>(xp + nb * 256 + MP * 16);
                     acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb],
                                                                       0, 0, 0);
                     acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1), acc[nb],
@@ -486,15 +498,16 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 const bf16x8 a0 = __builtin_bit_cast(bf16x8, wv);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const u32x4 b0 = xs[(piece0 + g) * MP + xm + 16 * nb];
+                    const u32x4 b0 = *reinterpret_cast<const u32x4 *>(xp + nb * 256);
                     acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb],
                                                                       0, 0, 0);
                 }
-                ring[d] = ring_refill(l_addr(), wv);
-                l_advance();
+                ring[d] = ring_refill_at(l_base, voff, wv);
+                l_base += l_inc;
+                if (__builtin_expect(--l_left == 0, 0)) l_event();
             }
             QUASAR_TRACE_SLOT(4)
-            if (c_si == c_nsl - 1) {
+            if (__builtin_expect(--c_left == 0, 0)) {
                 // ---- tile end: cross-wave sum through LDS, fixed order
                 f32x4 *st = stage + (parity * NW) * NB * 64;
 #pragma unroll
@@ -550,12 +563,23 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 }
                 parity ^= 1;
                 QUASAR_TRACE_SLOT(5)
-            }
-            // advance the compute front
-            if (++c_si >= c_nsl) {
-                c_si = 0;
-                if (++c_tl >= c_ntiles) { need_enter = true; QUASAR_TRACE(5) }
-                else if (__builtin_expect(c_t0 + c_tl == c_seg_end, 0)) c_reseg();
+                // advance the compute front
+                if (++c_tl >= c_ntiles) {
+                    QUASAR_TRACE(5)
+                    if (c_enter()) {
+                        c_left = c_nsl;
+                        c_xoff = c_x0;
+                    } else {
+                        running = false;
+                        c_left = kForever;
+                        c_xoff = 0u;
+                        c_xinc = 0u;
+                    }
+                } else {
+                    if (__builtin_expect(c_t0 + c_tl == c_seg_end, 0)) c_reseg();
+                    c_left = c_nsl;
+                    c_xoff = c_x0;
+                }
             }
         }
     }
