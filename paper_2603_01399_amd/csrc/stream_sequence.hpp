@@ -13,9 +13,10 @@
 //
 // Each wave walks ONE flat sequence of slots over the whole step:
 //     for phase, for K chunk, for tile of this workgroup, for step of this wave's K slice
-// (at least one slot per tile so that all waves meet at every tile end).  Slot j is loaded
-// into ring[j % D] exactly D slots before it is consumed, with no padding between phases, so
-// the ring always holds D real weight loads, many of them belonging to later phases.
+// (at least one slot per tile so that all waves meet at every tile end; the slots of one
+// (phase, chunk) are padded with slots of zeros to a multiple of D).  Slot j is loaded into
+// ring[j % D] D slots before it is consumed, so the ring holds the weights of the following
+// phases while the workgroup waits for activations.
 #pragma once
 
 #include "stream_gemm.hpp"
@@ -133,7 +134,7 @@ __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int ta
             ((unsigned long long)__builtin_amdgcn_s_getreg(6164) << 60) |                           \
             ((unsigned long long)(__builtin_amdgcn_s_getreg(63492) & 0xFFFF) << 44);
 #define QUASAR_TRACE_SLOT(tag)                                                                      \
-    if (b == 0 && tid == 0 && trace_n < 2000) {                                                     \
+    if (b == 0 && tid == 64 && trace_n < 2000) {                                                     \
         reinterpret_cast<unsigned long long *>(sp.partial)[80000 + trace_n] =                       \
             ((unsigned long long)(tag) << 56) | (__builtin_readcyclecounter() & 0x00FFFFFFFFFFFFFFull); \
         ++trace_n;                                                                                  \
@@ -143,6 +144,10 @@ __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int ta
 #define QUASAR_TRACE_SLOT(tag)
 #endif
 
+#ifndef QUASAR_SEQ_XB
+#define QUASAR_SEQ_XB 8
+#endif
+
 template <int MP, bool W16, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParams sp) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -150,7 +155,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     constexpr int PPS = W16 ? 4 : 8;
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
     constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
-    constexpr int XB = 8;
+    constexpr int XB = QUASAR_SEQ_XB;
     constexpr int nthreads = NW * 64;
     static_assert(NW == 16, "the in-kernel second stage of the verify phase assumes 1024 threads");
 
@@ -226,11 +231,23 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
         if (l_ph < nph && l_spw > 0) { l_base = l_wt; l_inc = 1024u; l_left = l_spw; }
         else { l_base = zeros; l_inc = 0u; l_left = l_ph < nph ? 1 : kForever; }
     };
+    // a wave's slots of one (phase, chunk) - a "unit" - are padded with slots of zeros to a
+    // multiple of D, so that every unit starts at ring[0]
+    bool l_in_pad = false;
     auto l_event = [&]() {
         if (l_ph < nph) {
-            if (++l_tl < l_ntiles) {
+            if (!l_in_pad && ++l_tl < l_ntiles) {
                 if (l_t0 + l_tl == l_seg_end) l_retile(); else l_wt += l_stride;
             } else {
+                const int pad = l_in_pad ? 0 : (-(l_ntiles * max(l_spw, 1))) & (D - 1);
+                if (pad > 0) {
+                    l_in_pad = true;
+                    l_base = zeros;
+                    l_inc = 0u;
+                    l_left = pad;
+                    return;
+                }
+                l_in_pad = false;
                 l_next();
             }
         }
@@ -310,12 +327,21 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             }
         }
     };
-    // wait until every workgroup has raised its flag for phase `pp` in this launch
+    // wait (wave 0 polls, four flags per lane and round trip) until every workgroup has raised
+    // its flag for phase `pp` in this launch
     auto flags_wait = [&](int pp) {
-        for (int t = tid; t < G; t += nthreads) {
+        if (w != 0) return;
+        const unsigned int *row = sp.flags + (long long)pp * G;
+        for (int t0 = 4 * lane; t0 < G; t0 += 256) {
             unsigned int spins = 0;
-            while (__hip_atomic_load(as_global(sp.flags + (long long)pp * G + t), __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+            for (;;) {
+                unsigned int f[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    f[i] = t0 + i < G ? __hip_atomic_load(as_global(row + t0 + i), __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_AGENT)
+                                      : epoch;
+                if (f[0] == epoch && f[1] == epoch && f[2] == epoch && f[3] == epoch) break;
                 if (++spins > sp.spin_limit ||
                     __hip_atomic_load(as_global(&sp.sync[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
                     __hip_atomic_store(as_global(&sp.sync[1]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -336,17 +362,24 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             }
         }
     };
-    // end of a phase: publish argmax partials and run the second stage
+    bool stored = false;   // this wave has output stores in flight
+    // end of a phase: raise this workgroup's completion flag if a later phase waits for it
     auto phase_end = [&](int ph) {
-        const auto &P = phases[ph];
-        if (P.publish) {
-            // every wave's output stores have been acknowledged before the flag goes up
-            __builtin_amdgcn_s_waitcnt(0x0F70);
+        if (phases[ph].publish) {
+            // the output stores have been acknowledged before the flag goes up (only waves that
+            // stored wait: for the others this would be a wait for their weight loads)
+            if (stored) __builtin_amdgcn_s_waitcnt(0x0F70);
+            stored = false;
             lds_barrier();
             if (tid == 0)
                 __hip_atomic_store(as_global(sp.flags + (long long)ph * G + b), epoch, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
+    };
+    // after the last phase, if it was the vocabulary phase: publish argmax partials, meet, and
+    // let workgroup 0 reduce them and compare with the draft
+    auto verify_second_stage = [&]() {
+        const auto &P = phases[nph - 1];
         if (P.kind != EPI_ARGMAX) return;
         unsigned long long *red = reinterpret_cast<unsigned long long *>(stage);   // [NW][MP]
         lds_barrier();
@@ -407,16 +440,21 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             lds_barrier();
         }
     };
+    bool nocomp = false;      // padding slots: no arithmetic
+    int unit_left = 0;        // slots (padded) left in the current unit
+    // the current (phase, chunk) is done
+    auto c_leave = [&]() {
+        ++c_c;
+        if (c_ph < nph && c_c >= c_C) {
+            phase_end(c_ph);
+            ++c_ph;
+            c_c = 0;
+        }
+    };
     // enter the next (phase, chunk): take part in the phase's wait, stage scales and
     // activations.  Returns false when the sequence is finished.
     auto c_enter = [&]() -> bool {
         for (;;) {
-            ++c_c;
-            if (c_ph < nph && c_c >= c_C) {
-                phase_end(c_ph);
-                ++c_ph;
-                c_c = 0;
-            }
             if (c_ph >= nph) return false;
             const auto &P = phases[c_ph];
             if (c_c == 0) {
@@ -435,7 +473,11 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     }
                     lds_barrier();   // flags seen by all; the previous phase's last epilogue has read its scales
                 }
-                if (c_ntiles == 0) { c_c = c_C - 1; continue; }   // nothing to do here but the waits
+                if (c_ntiles == 0) {   // nothing to do here but the waits
+                    c_c = c_C - 1;
+                    c_leave();
+                    continue;
+                }
                 scale_stage(P, c_t0, c_ntiles);
             }
             const int scc = min(P.SC, P.S - c_c * P.SC);
@@ -445,6 +487,10 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             c_xinc = spw > 0 ? (unsigned int)(PPS * MP * 16) : 0u;
             c_x0 = spw > 0 ? (unsigned int)s_lo * (unsigned int)(PPS * MP * 16) : 0u;
             c_tl = 0;
+            c_left = c_nsl;
+            c_xoff = c_x0;
+            unit_left = (c_ntiles * c_nsl + D - 1) & ~(D - 1);
+            nocomp = false;
             c_reseg();
             QUASAR_TRACE(1)
             x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
@@ -457,57 +503,51 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             return true;
         }
     };
-
-    // The rare paths (end of a run, end of a tile, entry into the next phase or chunk) are
-    // inlined into every slot of the unrolled round (the build raises the compiler's
-    // pragma-unroll size limit for this): any other shape - a side exit from the round, or
-    // re-entering it through a switch - makes the compiler lose count of the outstanding ring
-    // loads and drain the ring.  After the last phase the rest of the round consumes slots of
-    // zeros.
+    // Units start at a round boundary, so the entry code exists once, in front of the round.
+    // The end of a run and the end of a tile can fall on any slot and are inlined into every
+    // slot of the unrolled round (the build raises the compiler's pragma-unroll size limit for
+    // this): any other shape - a side exit from the round, or re-entering it through a switch -
+    // makes the compiler lose count of the outstanding ring loads and drain the ring.
 #ifdef QUASAR_SEQ_TRACE
     int trace_n = 0;
 #endif
     const unsigned char *xsb = lds;
-    bool running = c_enter();
-    if (running) { c_left = c_nsl; c_xoff = c_x0; }
-    while (running) {
+    c_leave();
+    for (;;) {
+        // ---- round boundary: units begin and end here
+        if (unit_left == 0 && !c_enter()) break;
+        unit_left -= D;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             QUASAR_TRACE_SLOT(1)
             const u32x4 wv = ring[d];
             const unsigned char *xp = xsb + (xlane + c_xoff);
-            c_xoff += c_xinc;
+            const unsigned long long la = l_base;
+            bf16x8 a0, a1;
             if constexpr (!W16) {
-                const bf16x8 a0 = codes_to_bf16x8(wv.x, wv.y);
-                const bf16x8 a1 = codes_to_bf16x8(wv.z, wv.w);
-                QUASAR_TRACE_SLOT(2)
-                ring[d] = ring_refill_at(l_base, voff, wv);
-                l_base += l_inc;
-                if (__builtin_expect(--l_left == 0, 0)) l_event();
-                QUASAR_TRACE_SLOT(3)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const u32x4 b0 = *reinterpret_cast<const u32x4 *>(xp + nb * 256);
-                    const u32x4 b1 = *reinterpret_cast<const u32x4 *>(xp + nb * 256 + MP * 16);
-                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb],
-                                                                      0, 0, 0);
-                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1), acc[nb],
-                                                                      0, 0, 0);
-                }
+                a0 = codes_to_bf16x8(wv.x, wv.y);
+                a1 = codes_to_bf16x8(wv.z, wv.w);
+                ring[d] = ring_refill_at(la, voff, wv);
             } else {
-                const bf16x8 a0 = __builtin_bit_cast(bf16x8, wv);
+                a0 = __builtin_bit_cast(bf16x8, wv);
+            }
+            if (!nocomp) {
+                c_xoff += c_xinc;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     const u32x4 b0 = *reinterpret_cast<const u32x4 *>(xp + nb * 256);
-                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb],
-                                                                      0, 0, 0);
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb], 0, 0, 0);
+                    if constexpr (!W16) {
+                        const u32x4 b1 = *reinterpret_cast<const u32x4 *>(xp + nb * 256 + MP * 16);
+                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1), acc[nb], 0, 0, 0);
+                    }
                 }
-                ring[d] = ring_refill_at(l_base, voff, wv);
-                l_base += l_inc;
-                if (__builtin_expect(--l_left == 0, 0)) l_event();
             }
+            if constexpr (W16) ring[d] = ring_refill_at(la, voff, wv);
+            l_base += l_inc;
+            if (__builtin_expect(--l_left == 0, 0)) l_event();
             QUASAR_TRACE_SLOT(4)
-            if (__builtin_expect(--c_left == 0, 0)) {
+            if (!nocomp && __builtin_expect(--c_left == 0, 0)) {
                 // ---- tile end: cross-wave sum through LDS, fixed order
                 f32x4 *st = stage + (parity * NW) * NB * 64;
 #pragma unroll
@@ -516,7 +556,10 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
                 lds_barrier();
-                if (w == (c_tl % NW)) {
+                // the epilogue rotates over waves 1..NW-1: wave 0 polls for the next phase's input
+                // and should never have to wait for its own stores
+                if (w == 1 + (c_tl % (NW - 1))) {
+                    stored = true;
                     f32x4 rsum[NB];
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
@@ -563,18 +606,11 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 }
                 parity ^= 1;
                 QUASAR_TRACE_SLOT(5)
-                // advance the compute front
+                // advance the compute front; after the unit's last tile only padding is left
                 if (++c_tl >= c_ntiles) {
+                    nocomp = true;
                     QUASAR_TRACE(5)
-                    if (c_enter()) {
-                        c_left = c_nsl;
-                        c_xoff = c_x0;
-                    } else {
-                        running = false;
-                        c_left = kForever;
-                        c_xoff = 0u;
-                        c_xinc = 0u;
-                    }
+                    c_leave();
                 } else {
                     if (__builtin_expect(c_t0 + c_tl == c_seg_end, 0)) c_reseg();
                     c_left = c_nsl;
@@ -583,6 +619,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             }
         }
     }
+    verify_second_stage();
 }
 
 // Runs ahead of every sequence launch: clears the barrier counter and the error flag and
