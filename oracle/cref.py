@@ -36,6 +36,10 @@ class CRef:
         self.lib.qref_bf16_linear.restype = None
         self.lib.qref_lmhead_verify.argtypes = [vp, i64, i64, vp, vp, i64, vp, i64, vp]
         self.lib.qref_lmhead_verify.restype = ctypes.c_int32
+        self.lib.qref_quantize_activations.argtypes = [vp, i64, i64, vp, vp, vp]
+        self.lib.qref_quantize_activations.restype = None
+        self.lib.qref_w8a8_logits.argtypes = [vp, vp, i64, i64, vp, vp, i64, vp]
+        self.lib.qref_w8a8_logits.restype = ctypes.c_int32
 
     @staticmethod
     def _p(a):
@@ -79,6 +83,33 @@ class CRef:
         n = self.lib.qref_lmhead_verify(self._p(h_bits), M, K, self._p(q), self._p(s_bits), V,
                                         self._p(draft), draft.size, self._p(arg))
         return arg, int(n)
+
+
+    def quantize_activations(self, x_bits, smooth=None):
+        x_bits = np.ascontiguousarray(x_bits, dtype=np.uint16)
+        M, K = x_bits.shape
+        sp = None
+        if smooth is not None:
+            smooth = np.ascontiguousarray(smooth, dtype=np.float32)
+            sp = self._p(smooth)
+        xq = np.empty((M, K), dtype=np.int8)
+        dx = np.empty(M, dtype=np.float32)
+        self.lib.qref_quantize_activations(self._p(x_bits), M, K, sp, self._p(xq), self._p(dx))
+        return xq, dx
+
+    def w8a8_logits(self, xq, dx, q, dw_bits):
+        xq = np.ascontiguousarray(xq, dtype=np.int8)
+        dx = np.ascontiguousarray(dx, dtype=np.float32)
+        q = np.ascontiguousarray(q, dtype=np.int8)
+        dw_bits = np.ascontiguousarray(dw_bits, dtype=np.uint16)
+        M, K = xq.shape
+        N = q.shape[0]
+        out = np.empty((M, N), dtype=np.float32)
+        ovf = self.lib.qref_w8a8_logits(self._p(xq), self._p(dx), M, K, self._p(q), self._p(dw_bits), N,
+                                        self._p(out))
+        if ovf:
+            raise OverflowError("int32 accumulator overflow")
+        return out
 
 
 _cached = None

@@ -107,3 +107,66 @@ int32_t qref_lmhead_verify(const uint16_t *h_bits, int64_t M, int64_t K,
     }
     return n_acc;
 }
+
+/* ---------------------------------------------------------------------------------------
+ * W8A8 form (Sec. 3.2 "Quantized Inference"; Sec. 3.3 online activation smoothing and
+ * quantisation, INT8 gemm and dequantisation, Eq. 10).  One IEEE fp32 operation per step,
+ * in the order of the numpy form; integer products summed in 64-bit and checked to fit
+ * int32 by the caller.
+ * ------------------------------------------------------------------------------------- */
+static float bf16_to_float(uint16_t b) {
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* x[M,K] bf16 (+ optional s[K] fp32) -> xq[M,K] int8, dx[M] fp32 */
+void qref_quantize_activations(const uint16_t *x_bits, int64_t M, int64_t K, const float *smooth,
+                               int8_t *xq, float *dx) {
+    for (int64_t m = 0; m < M; ++m) {
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; ++k) {
+            volatile float xt = bf16_to_float(x_bits[m * K + k]);
+            if (smooth) xt = xt * smooth[k];
+            float a = fabsf(xt);
+            if (a > amax) amax = a;
+        }
+        if (!(amax > 0.0f)) {
+            dx[m] = 0.0f;
+            for (int64_t k = 0; k < K; ++k) xq[m * K + k] = 0;
+            continue;
+        }
+        volatile float step = amax / 127.0f;
+        volatile float inv = 127.0f / amax;
+        dx[m] = step;
+        for (int64_t k = 0; k < K; ++k) {
+            volatile float xt = bf16_to_float(x_bits[m * K + k]);
+            if (smooth) xt = xt * smooth[k];
+            volatile float pr = xt * inv;
+            float r = nearbyintf(pr);
+            if (r > 127.0f) r = 127.0f;
+            if (r < -127.0f) r = -127.0f;
+            xq[m * K + k] = (int8_t)r;
+        }
+    }
+}
+
+/* logits[M,N] fp32 = fp32(sum_k xq*q) * (dx[m] * dw[n]); returns 0, or 1 if a sum left int32 */
+int32_t qref_w8a8_logits(const int8_t *xq, const float *dx, int64_t M, int64_t K,
+                         const int8_t *q, const uint16_t *dw_bits, int64_t N, float *out) {
+    int32_t overflow = 0;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k) acc += (int64_t)xq[m * K + k] * (int64_t)q[n * K + k];
+            if (acc > 2147483647LL || acc < -2147483648LL) overflow = 1;
+            volatile float scale = dx[m] * bf16_to_float(dw_bits[n]);
+            volatile float a = (float)(int32_t)acc;
+            volatile float y = a * scale;
+            out[m * N + n] = y;
+        }
+    return overflow;
+}
+
+uint16_t qref_float_to_bf16(float f) { return float_to_bf16_rne(f); }
