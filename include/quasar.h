@@ -200,6 +200,59 @@ int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device,
                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * ---- W8A8 form: int8 codes on both sides (Sec. 3.2 "Smoothing Transformation" and
+ * "Quantized Inference"; Sec. 3.3 "Online Activation Smoothing and Quantization",
+ * "INT8 Gemm and Dequantization", Eq. 10) ----
+ *
+ * `smooth` is the per-input-channel factor vector s of the smoothing transformation:
+ * device, [K] fp32, 16-byte aligned, or NULL for none.  Offline the weights take
+ * W diag(s)^-1, online the activations take X (.) s; calibrating s is not part of this
+ * library.  Every floating-point step that decides a code or the result bits is one IEEE
+ * fp32 operation (round to nearest even), in this order:
+ *     x~[m,k] = float(x[m,k]) * s[k]
+ *     amax_m = max_k |x~[m,k]|;  dx_m = amax_m / 127;  inv_m = 127 / amax_m
+ *     x^[m,k] = clamp(rint(x~[m,k] * inv_m), -127, 127)        (a zero row: dx = 0, codes 0)
+ *     acc[m,n] = sum_k x^[m,k] * q[n,k]                        (int32, exact)
+ *     y[m,n]  = bf16( float(acc[m,n]) * (dx_m * dw_n) )
+ * so results are reproducible bit for bit.  Non-finite inputs give unspecified values.
+ */
+
+/* Offline weight preparation with the smoothing divide (Sec. 3.3 "Offline Weight
+ * Preparation": W_int8 = Q(W diag(s)^-1)): as quasar_quantize_weights, applied to
+ * fp32(W[n,k] / s[k]).  smooth NULL = quasar_quantize_weights. */
+int quasar_quantize_weights_smoothed(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw,
+                                     const float *smooth, int8_t *wq_packed, uint16_t *scales_bf16,
+                                     void *hip_stream);
+
+/* The activation quantiser on its own (Sec. 3.3 "Online Activation Smoothing and
+ * Quantization", X_int8 = Q(X (.) s, delta_x)), one step size per token.
+ *   x     device, [M, K] bf16, row stride ldx (multiple of 8), 16-byte aligned
+ *   xq    device out, [M, K] int8 row-major, 8-byte aligned
+ *   dx    device out, [M] fp32 step sizes
+ * The fused entry points below run the same arithmetic internally; this one makes the
+ * codes observable. */
+int quasar_quantize_activations(const uint16_t *x, int64_t M, int64_t K, int64_t ldx,
+                                const float *smooth, int8_t *xq, float *dx, void *hip_stream);
+
+/* W8A8 linear layer: activation smoothing + quantisation, int8 x int8 matrix-core
+ * contraction with int32 sums, dequantisation by (delta_w . delta_x) (Eq. 10), one launch.
+ * Arguments as quasar_w8_linear plus `smooth`; workspace unused (may be NULL). */
+int quasar_w8a8_linear(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const float *smooth,
+                       const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t N,
+                       uint16_t *y, int64_t ldy,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* W8A8 vocabulary projection fused with the acceptance decision (Eq. 10 logits kept in
+ * fp32, then Eq. 2 at temperature 0 as in quasar_lmhead_verify).  Arguments as
+ * quasar_lmhead_verify plus `smooth`. */
+int quasar_w8a8_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh,
+                              const float *smooth,
+                              const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t V,
+                              const int32_t *draft_ids, int64_t n_draft,
+                              int32_t *out_argmax, int32_t *out_accept_len,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Measurement helpers (the bandwidth term of Eq. 11-12 measured directly).
  * quasar_read_stream reads `bytes` (multiple of 16) from `src` with the same
  * load pattern as the linear kernels and writes one checksum word per workgroup

@@ -95,15 +95,21 @@ def quantize_activations(x_bits, smooth=None):
 
 def w8a8_accumulate(xq, q) -> np.ndarray:
     """acc[m, n] = sum_k x^[m, k] * q[n, k], exact; must fit int32 (it does for
-    K <= 133000 since every product is at most 127 * 127)."""
+    K <= 133000 since every product is at most 127 * 127).
+
+    The sum is taken by the fp64 matrix product: every product is an integer below 2^14
+    and every partial sum an integer below 2^31 * ... < 2^53, so no rounding can occur in
+    any summation order (pinned against pure-Python integer sums in the tests)."""
     xq = np.ascontiguousarray(xq, dtype=np.int8)
     q = np.ascontiguousarray(q, dtype=np.int8)
     if xq.ndim != 2 or q.ndim != 2 or xq.shape[1] != q.shape[1]:
         raise ValueError("shape mismatch: xq[M,K], q[N,K]")
-    acc = xq.astype(np.int64) @ q.astype(np.int64).T
+    if xq.shape[1] > 2 ** 38:
+        raise OverflowError("K too large for exact fp64 summation")
+    acc = xq.astype(np.float64) @ q.astype(np.float64).T
     if acc.size and (acc.max() > 2**31 - 1 or acc.min() < -2**31):
         raise OverflowError("int32 accumulator overflow")
-    return acc.astype(np.int32)
+    return acc.astype(np.int64).astype(np.int32)
 
 
 def w8a8_scale(dw_bits, dx) -> np.ndarray:

@@ -27,6 +27,8 @@ EXPORTS = (
     "quasar_read_stream", "quasar_copy_stream",
     "quasar_sequence_plan_bytes", "quasar_sequence_workspace_bytes", "quasar_sequence_prepare",
     "quasar_sequence_run",
+    "quasar_quantize_weights_smoothed", "quasar_quantize_activations", "quasar_w8a8_linear",
+    "quasar_w8a8_lmhead_verify",
 )
 
 
@@ -88,6 +90,10 @@ def _load() -> ctypes.CDLL:
     lib.quasar_sequence_workspace_bytes.restype = sz
     lib.quasar_sequence_prepare.argtypes = [vp, i64, vp, i64, vp, sz, vp, sz, vp]
     lib.quasar_sequence_run.argtypes = [vp, vp, vp, sz, vp]
+    lib.quasar_quantize_weights_smoothed.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.quasar_quantize_activations.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
+    lib.quasar_w8a8_linear.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, sz, vp]
+    lib.quasar_w8a8_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, vp, vp, sz, vp]
     return lib
 
 
@@ -167,6 +173,88 @@ def quantize_weights(w: torch.Tensor, wq_packed: torch.Tensor = None, scales: to
     _check("quasar_quantize_weights",
            _lib.quasar_quantize_weights(_ptr(w), dt, N, K, w.stride(0), _ptr(wq_packed), _ptr(scales), _stream()))
     return wq_packed, scales
+
+
+def quantize_weights_smoothed(w: torch.Tensor, smooth: torch.Tensor, wq_packed: torch.Tensor = None,
+                              scales: torch.Tensor = None):
+    """As quantize_weights, applied to W diag(s)^-1 (smooth [K] fp32, or None)."""
+    _dev(w, "w")
+    if w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be [N, K] with a contiguous last dimension")
+    dt = {torch.float32: F32, torch.bfloat16: BF16}.get(w.dtype)
+    if dt is None:
+        raise TypeError("w must be float32 or bfloat16")
+    N, K = w.shape
+    if smooth is not None:
+        _dev(smooth, "smooth", torch.float32)
+        if smooth.numel() != K or not smooth.is_contiguous():
+            raise ValueError("smooth must be a contiguous [K] vector")
+    if wq_packed is None:
+        wq_packed = torch.empty(max(packed_bytes(N, K), 1), dtype=torch.int8, device=w.device)
+    if scales is None:
+        scales = torch.empty(N, dtype=torch.bfloat16, device=w.device)
+    _check("quasar_quantize_weights_smoothed",
+           _lib.quasar_quantize_weights_smoothed(_ptr(w), dt, N, K, w.stride(0), _ptr(smooth), _ptr(wq_packed),
+                                                 _ptr(scales), _stream()))
+    return wq_packed, scales
+
+
+def _smooth_arg(smooth, K):
+    if smooth is None:
+        return None
+    _dev(smooth, "smooth", torch.float32)
+    if smooth.numel() != K or not smooth.is_contiguous():
+        raise ValueError("smooth must be a contiguous [K] vector")
+    return _ptr(smooth)
+
+
+def quantize_activations(x: torch.Tensor, smooth: torch.Tensor = None):
+    """x [M, K] bf16 -> (codes int8 [M, K], step sizes fp32 [M])."""
+    _dev(x, "x", torch.bfloat16)
+    M, K = x.shape
+    xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    dx = torch.empty(M, dtype=torch.float32, device=x.device)
+    _check("quasar_quantize_activations",
+           _lib.quasar_quantize_activations(_ptr(x), M, K, x.stride(0), _smooth_arg(smooth, K), _ptr(xq), _ptr(dx),
+                                            _stream()))
+    return xq, dx
+
+
+def w8a8_linear(x: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Tensor, N: int,
+                smooth: torch.Tensor = None, y: torch.Tensor = None) -> torch.Tensor:
+    _dev(x, "x", torch.bfloat16)
+    _dev(wq_packed, "wq_packed", torch.int8)
+    _dev(scales, "scales", torch.bfloat16)
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _check("quasar_w8a8_linear",
+           _lib.quasar_w8a8_linear(_ptr(x), M, K, x.stride(0), _smooth_arg(smooth, K), _ptr(wq_packed), _ptr(scales),
+                                   N, _ptr(y), y.stride(0), None, 0, _stream()))
+    return y
+
+
+def w8a8_lmhead_verify(hidden: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Tensor, V: int,
+                       draft_ids: torch.Tensor, workspace: torch.Tensor, smooth: torch.Tensor = None,
+                       out_argmax: torch.Tensor = None, out_accept: torch.Tensor = None):
+    _dev(hidden, "hidden", torch.bfloat16)
+    _dev(wq_packed, "wq_packed", torch.int8)
+    _dev(scales, "scales", torch.bfloat16)
+    M, K = hidden.shape
+    n_draft = 0 if draft_ids is None else draft_ids.numel()
+    if n_draft:
+        _dev(draft_ids, "draft_ids", torch.int32)
+    if out_argmax is None:
+        out_argmax = torch.empty(M, dtype=torch.int32, device=hidden.device)
+    if out_accept is None:
+        out_accept = torch.empty(1, dtype=torch.int32, device=hidden.device)
+    _check("quasar_w8a8_lmhead_verify",
+           _lib.quasar_w8a8_lmhead_verify(_ptr(hidden), M, K, hidden.stride(0), _smooth_arg(smooth, K),
+                                          _ptr(wq_packed), _ptr(scales), V,
+                                          _ptr(draft_ids) if n_draft else None, n_draft, _ptr(out_argmax),
+                                          _ptr(out_accept), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream()))
+    return out_argmax, out_accept
 
 
 def unpack_weights(wq_packed: torch.Tensor, N: int, K: int) -> torch.Tensor:

@@ -20,14 +20,20 @@ __device__ __forceinline__ float load_w(const void *w, long long idx) {
     else
         return reinterpret_cast<const float *>(w)[idx];
 }
+// element k of a row, with the offline side of the smoothing transformation applied
+// (W diag(s)^-1, one fp32 division) when a smoothing vector is given
+template <bool SRC_BF16>
+__device__ __forceinline__ float load_w_smoothed(const void *w, long long row_base, int k, const float *smooth) {
+    const float v = load_w<SRC_BF16>(w, row_base + k);
+    return smooth ? __fdiv_rn(v, smooth[k]) : v;
+}
 
 // One workgroup (256 threads) per 16-row tile.
 template <bool SRC_BF16>
 __global__ __launch_bounds__(256) void quantize_pack_kernel(const void *w, long long ldw, int N, int K,
-                                                            u32x4 *packed, uint16_t *scales) {
-    __shared__ float red[4][kTileRows];
+                                                            const float *smooth, u32x4 *packed, uint16_t *scales) {
     __shared__ float row_scale[kTileRows];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     const int t = blockIdx.x;
     const int S = K / kStepK8;
 
@@ -36,7 +42,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const void *w, long 
         const int r = tid >> 4, c = tid & 15;
         const long long base = (long long)(t * kTileRows + r) * ldw;
         float amax = 0.f;
-        for (int k = c; k < K; k += 16) amax = fmaxf(amax, fabsf(load_w<SRC_BF16>(w, base + k)));
+        for (int k = c; k < K; k += 16) amax = fmaxf(amax, fabsf(load_w_smoothed<SRC_BF16>(w, base, k, smooth)));
 #pragma unroll
         for (int off = 8; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
         if (c == 0) {
@@ -48,7 +54,6 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const void *w, long 
             scales[t * kTileRows + r] = (uint16_t)sb;
         }
     }
-    (void)red; (void)lane; (void)wave;
     __syncthreads();
 
     // pass 2: each thread produces one 16-byte lane slot of one step at a time
@@ -56,7 +61,8 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const void *w, long 
         const int s = slot >> 6, l = slot & 63;
         const int g = l >> 4, i = l & 15;
         const float sc = row_scale[i];
-        const long long base = (long long)(t * kTileRows + i) * ldw + (long long)s * kStepK8 + 16 * g;
+        const long long base = (long long)(t * kTileRows + i) * ldw;
+        const int k0 = s * kStepK8 + 16 * g;
         unsigned int out[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -65,7 +71,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const void *w, long 
             for (int e = 0; e < 4; ++e) {
                 int code = 0;
                 if (sc > 0.f) {
-                    const float ratio = __fdiv_rn(load_w<SRC_BF16>(w, base + 4 * q + e), sc);
+                    const float ratio = __fdiv_rn(load_w_smoothed<SRC_BF16>(w, base, k0 + 4 * q + e, smooth), sc);
                     float r = rintf(ratio);                 // round half to even
                     r = fminf(fmaxf(r, -127.f), 127.f);
                     code = (int)r;

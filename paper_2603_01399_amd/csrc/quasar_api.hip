@@ -15,6 +15,7 @@
 #include "probe.hpp"
 #include "stream_gemm.hpp"
 #include "stream_sequence.hpp"
+#include "stream_w8a8.hpp"
 
 using namespace quasar;
 
@@ -282,23 +283,30 @@ size_t quasar_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     return (size_t)kMaxGrid * 32u * sizeof(unsigned long long);
 }
 
-int quasar_quantize_weights(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw, int8_t *wq_packed,
-                            uint16_t *scales_bf16, void *hip_stream) {
+int quasar_quantize_weights_smoothed(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw,
+                                     const float *smooth, int8_t *wq_packed, uint16_t *scales_bf16,
+                                     void *hip_stream) {
     if (!w || !wq_packed || !scales_bf16) return QUASAR_ERR_NULL;
     if (w_dtype != QUASAR_F32 && w_dtype != QUASAR_BF16) return QUASAR_ERR_DTYPE;
     if (const int e = check_mnk(1, N, K)) return e;
     if (ldw < K) return QUASAR_ERR_SHAPE;
-    if (!aligned(wq_packed, 16) || !aligned(scales_bf16, 2) || !aligned(w, w_dtype == QUASAR_F32 ? 4 : 2))
+    if (!aligned(wq_packed, 16) || !aligned(scales_bf16, 2) || !aligned(w, w_dtype == QUASAR_F32 ? 4 : 2) ||
+        !aligned(smooth, 4))
         return QUASAR_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int T = (int)(N / kTileRows);
     if (w_dtype == QUASAR_F32)
         hipLaunchKernelGGL(quantize_pack_kernel<false>, dim3(T), dim3(256), 0, st, w, (long long)ldw, (int)N, (int)K,
-                           reinterpret_cast<u32x4 *>(wq_packed), scales_bf16);
+                           smooth, reinterpret_cast<u32x4 *>(wq_packed), scales_bf16);
     else
         hipLaunchKernelGGL(quantize_pack_kernel<true>, dim3(T), dim3(256), 0, st, w, (long long)ldw, (int)N, (int)K,
-                           reinterpret_cast<u32x4 *>(wq_packed), scales_bf16);
+                           smooth, reinterpret_cast<u32x4 *>(wq_packed), scales_bf16);
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+int quasar_quantize_weights(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw, int8_t *wq_packed,
+                            uint16_t *scales_bf16, void *hip_stream) {
+    return quasar_quantize_weights_smoothed(w, w_dtype, N, K, ldw, nullptr, wq_packed, scales_bf16, hip_stream);
 }
 
 int quasar_unpack_weights(const int8_t *wq_packed, int64_t N, int64_t K, int8_t *q_rowmajor, void *hip_stream) {
@@ -422,6 +430,25 @@ bool plan_phase(SeqPhase &ph, int MP, bool w16, int G, int &xs_bytes, int &sc_by
     sc_bytes = w16 ? 0 : ((tpw * kTileRows * 2 + 15) / 16) * 16;
     acc_bytes = ph.C > 1 ? tpw * NB * 1024 : 0;
     return true;
+}
+
+template <int EPI>
+int launch_w8a8(const GemmParams &base, int M, hipStream_t stream, int *grid_out) {
+    GemmParams p = base;
+    const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
+    const int NB = MP == 32 ? 2 : 1;
+    // int8 codes: 64 bytes of LDS per token and step; 256 bytes more for the per-token steps
+    Plan pl = make_plan(p.T, p.S, 64 * MP, NB * 1024, 16, true);
+    if (pl.grid > kMaxGrid) return QUASAR_ERR_SHAPE;
+    p.SC = pl.SC;
+    p.C = pl.C;
+    p.xs_bytes = pl.xs_bytes;
+    p.sc_bytes = pl.sc_bytes + 256;
+    const int lds = pl.lds_bytes + 256;
+    if (grid_out) *grid_out = pl.grid;
+    if (MP == 8) return launch(stream_w8a8_kernel<8, EPI, 16, 8>, pl.grid, 1024, lds, stream, p);
+    if (MP == 16) return launch(stream_w8a8_kernel<16, EPI, 16, 8>, pl.grid, 1024, lds, stream, p);
+    return launch(stream_w8a8_kernel<32, EPI, 16, 8>, pl.grid, 1024, lds, stream, p);
 }
 
 template <int MP, bool W16>
@@ -646,6 +673,65 @@ int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, voi
     if (h.MP == 8) return launch_sequence<8, false>(h, sp, st);
     if (h.MP == 16) return launch_sequence<16, false>(h, sp, st);
     return launch_sequence<32, false>(h, sp, st);
+}
+
+int quasar_quantize_activations(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const float *smooth,
+                                int8_t *xq, float *dx, void *hip_stream) {
+    if (!x || !xq || !dx) return QUASAR_ERR_NULL;
+    if (const int e = check_mnk(M, 16, K)) return e;
+    if (ldx < K || ldx % 8) return QUASAR_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(xq, 8) || !aligned(dx, 4) || !aligned(smooth, 16)) return QUASAR_ERR_ALIGN;
+    hipLaunchKernelGGL(quantize_activations_kernel, dim3((unsigned int)M), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), x, (long long)ldx, (int)K, smooth, xq, dx);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+int quasar_w8a8_linear(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const float *smooth,
+                       const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t N, uint16_t *y, int64_t ldy,
+                       void *workspace, size_t workspace_bytes, void *hip_stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (!x || !wq_packed || !scales_bf16 || !y) return QUASAR_ERR_NULL;
+    if (const int e = check_mnk(M, N, K)) return e;
+    if (ldx < K || ldy < N || ldx % 8 || ldy % 8) return QUASAR_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(wq_packed, 16) || !aligned(scales_bf16, 8) ||
+        !aligned(smooth, 16))
+        return QUASAR_ERR_ALIGN;
+    GemmParams p{};
+    p.x = x; p.ldx = ldx; p.w = reinterpret_cast<const u32x4 *>(wq_packed); p.scales = scales_bf16;
+    p.y = y; p.ldy = ldy; p.partial = nullptr; p.smooth = smooth;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.T = (int)(N / kTileRows);
+    p.S = (int)(K / kStepK8);
+    return launch_w8a8<EPI_LINEAR>(p, (int)M, static_cast<hipStream_t>(hip_stream), nullptr);
+}
+
+int quasar_w8a8_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh, const float *smooth,
+                              const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t V,
+                              const int32_t *draft_ids, int64_t n_draft, int32_t *out_argmax,
+                              int32_t *out_accept_len, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!hidden || !wq_packed || !scales_bf16 || !out_argmax || !out_accept_len) return QUASAR_ERR_NULL;
+    if (n_draft > 0 && !draft_ids) return QUASAR_ERR_NULL;
+    if (const int e = check_mnk(M, V, K)) return e;
+    if (V > 0x7FFFFFF0ll) return QUASAR_ERR_SHAPE;
+    if (n_draft < 0 || n_draft > M) return QUASAR_ERR_SHAPE;
+    if (ldh < K || ldh % 8) return QUASAR_ERR_SHAPE;
+    if (!aligned(hidden, 16) || !aligned(wq_packed, 16) || !aligned(scales_bf16, 8) || !aligned(smooth, 16))
+        return QUASAR_ERR_ALIGN;
+    if (!workspace || workspace_bytes < quasar_workspace_bytes(M, V, K)) return QUASAR_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return QUASAR_ERR_ALIGN;
+    GemmParams p{};
+    p.x = hidden; p.ldx = ldh; p.w = reinterpret_cast<const u32x4 *>(wq_packed); p.scales = scales_bf16;
+    p.y = nullptr; p.ldy = 0; p.partial = static_cast<unsigned long long *>(workspace); p.smooth = smooth;
+    p.M = (int)M; p.N = (int)V; p.K = (int)K;
+    p.T = (int)(V / kTileRows);
+    p.S = (int)(K / kStepK8);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int grid = 0;
+    if (const int e = launch_w8a8<EPI_ARGMAX>(p, (int)M, st, &grid)) return e;
+    const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
+    hipLaunchKernelGGL(verify_finalize_kernel, dim3(1), dim3(1024), 0, st, p.partial, grid, MP, (int)M, (int)V,
+                       draft_ids, (int)n_draft, out_argmax, out_accept_len);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
 }  // extern "C"

@@ -29,6 +29,7 @@ struct GemmParams {
     int C;          // number of K chunks
     int xs_bytes;   // LDS bytes reserved for the activation chunk
     int sc_bytes;   // LDS bytes reserved for the workgroup's row scales
+    const float *smooth;   // [K] per-channel smoothing factors of the W8A8 path (nullptr: none)
 };
 
 enum { EPI_LINEAR = 0, EPI_ARGMAX = 1 };
