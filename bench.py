@@ -262,6 +262,57 @@ def main() -> int:
             log(f"  cold {name:10s} {K:6d}->{N:6d}: {us:7.2f} us  {lin_bytes(K, N, 1) / us / 1e3:7.1f} GB/s "
                 f"({lin_bytes(K, N, 1) / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
             detail[f"cold_{name}_us"] = us
+        # the W8A8 form (activations quantised per token inside the kernel, int8 matrix cores),
+        # same weights, same cold walk through the layers' copies; then its vocabulary verify
+        for i, (name, K, N) in enumerate(shapes):
+            x = torch.randn((M, K), device=dev).to(torch.bfloat16)
+            y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            def go8():
+                for lin in layers:
+                    qb.w8a8_linear(x, lin[i][3], lin[i][4], N, y=y)
+            go8()
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                go8()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (3 * L)
+            log(f"  cold W8A8 {name:10s} {K:6d}->{N:6d}: {us:7.2f} us  {lin_bytes(K, N, 1) / us / 1e3:7.1f} GB/s "
+                f"({lin_bytes(K, N, 1) / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
+            detail[f"cold_w8a8_{name}_us"] = us
+        for label, fn in (("W8 x bf16", lambda: qb.lmhead_verify(h0, head_q, head_s, V, draft, ws, out_argmax,
+                                                                  out_accept)),
+                          ("W8A8", lambda: qb.w8a8_lmhead_verify(h0, head_q, head_s, V, draft, ws,
+                                                                 out_argmax=out_argmax, out_accept=out_accept))):
+            fn()
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 10
+            log(f"  vocabulary verify, single call, {label}: {us:7.2f} us  {head_bytes(1) / us / 1e3:7.1f} GB/s "
+                f"({head_bytes(1) / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
+            detail["head_verify_" + ("w8a8" if label == "W8A8" else "w8") + "_us"] = us
+        calls88 = []
+        for fn, a, nb, is_lin in calls8:
+            if is_lin:
+                x, wq, sc, N, y = a
+                calls88.append((lambda x=x, wq=wq, sc=sc, N=N, y=y: qb.w8a8_linear(x, wq, sc, N, y=y), (), nb, True))
+            else:
+                calls88.append((lambda: qb.w8a8_lmhead_verify(bufs[L - 1]["d"], head_q, head_s, V, draft, ws,
+                                                              out_argmax=out_argmax, out_accept=out_accept), (), nb,
+                                False))
+        us88 = time_steps(calls88, max(2, args.steps // 4), 1)
+        log(f"  W8A8 step as {len(calls88)} separate calls from Python: {us88:.1f} us "
+            f"(W8 x bf16 the same way: {us_calls:.1f} us)")
+        detail["w8a8_separate_calls_us_per_step"] = us88
         # VALU dot-product path against the MFMA path at small M (the measured crossover)
         gi = [i for i, sh in enumerate(shapes) if sh[0] == "gate_proj"][0]
         _, Kg, Ng = shapes[gi]

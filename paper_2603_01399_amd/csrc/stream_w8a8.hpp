@@ -125,7 +125,18 @@ __global__ __launch_bounds__(NW * 64) void stream_w8a8_kernel(const GemmParams p
     i32x4 *stage = reinterpret_cast<i32x4 *>(lds + p.xs_bytes + p.sc_bytes);          // [2][NW][NB][64]
     i32x4 *accs = stage + 2 * NW * NB * 64;                                            // [ntiles][NB][64] (C > 1)
 
-    // the weight ring first: its addresses depend on nothing
+    // requests in the order they are needed back: the first batch of activations (kept in
+    // registers for both passes below), then the weight ring
+    const int m_own = tid & (MP - 1);          // every thread always sees the same token
+    const int npieces_all = (p.K / 8) * MP;
+    u32x4 xfirst[XB];
+#pragma unroll
+    for (int i = 0; i < XB; ++i) {
+        const int idx = i * nthreads + tid;
+        xfirst[i] = u32x4{0u, 0u, 0u, 0u};
+        if (idx < npieces_all && m_own < p.M)
+            xfirst[i] = *reinterpret_cast<const u32x4 *>(p.x + m_own * p.ldx + 8ll * (idx >> LMP));
+    }
     WaveWalk<NW, D> walk{p, w, lane, t0, ntiles};
     typename WaveWalk<NW, D>::Front ld;
     walk.begin(ld);
@@ -136,55 +147,64 @@ __global__ __launch_bounds__(NW * 64) void stream_w8a8_kernel(const GemmParams p
         walk.advance(ld);
     }
 
-    // ---- per-token step sizes over the whole K (every thread always sees the same token)
-    const int m_own = tid & (MP - 1);
+    // ---- per-token step sizes over the whole K
     if (tid < 32) tok_amax[tid] = 0u;
     lds_barrier();
-    {
+    if (m_own < p.M) {
         float amax = 0.f;
-        const int npieces = (p.K / 8) * MP;
-        if (m_own < p.M) {
-            for (int base = 0; base < npieces; base += nthreads * XB) {
-                u32x4 v[XB];
 #pragma unroll
-                for (int i = 0; i < XB; ++i) {
-                    const int idx = base + i * nthreads + tid;
-                    v[i] = u32x4{0u, 0u, 0u, 0u};
-                    if (idx < npieces) v[i] = *reinterpret_cast<const u32x4 *>(p.x + m_own * p.ldx + 8ll * (idx >> LMP));
-                }
+        for (int i = 0; i < XB; ++i) {
+            const int idx = i * nthreads + tid;
+            if (idx < npieces_all) {
+                float xt[8];
+                smooth_piece(xfirst[i], p.smooth, 8ll * (idx >> LMP), xt);
+                amax = fmaxf(amax, piece_amax(xt));
+            }
+        }
+        for (int base = nthreads * XB; base < npieces_all; base += nthreads * XB) {
+            u32x4 v[XB];
 #pragma unroll
-                for (int i = 0; i < XB; ++i) {
-                    const int idx = base + i * nthreads + tid;
-                    if (idx < npieces) {
-                        float xt[8];
-                        smooth_piece(v[i], p.smooth, 8ll * (idx >> LMP), xt);
-                        amax = fmaxf(amax, piece_amax(xt));
-                    }
+            for (int i = 0; i < XB; ++i) {
+                const int idx = base + i * nthreads + tid;
+                v[i] = u32x4{0u, 0u, 0u, 0u};
+                if (idx < npieces_all) v[i] = *reinterpret_cast<const u32x4 *>(p.x + m_own * p.ldx + 8ll * (idx >> LMP));
+            }
+#pragma unroll
+            for (int i = 0; i < XB; ++i) {
+                const int idx = base + i * nthreads + tid;
+                if (idx < npieces_all) {
+                    float xt[8];
+                    smooth_piece(v[i], p.smooth, 8ll * (idx >> LMP), xt);
+                    amax = fmaxf(amax, piece_amax(xt));
                 }
             }
-            // non-negative floats order like their bit patterns
-            __hip_atomic_fetch_max(&tok_amax[m_own], __float_as_uint(amax), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_WORKGROUP);
         }
+        // non-negative floats order like their bit patterns
+        __hip_atomic_fetch_max(&tok_amax[m_own], __float_as_uint(amax), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     lds_barrier();
     const float amax_own = __uint_as_float(tok_amax[m_own]);
     const float inv = inverse_step_of(amax_own);
     if (tid < MP) tok_dx[tid] = step_of(amax_own);
 
-    // codes of K chunk c -> LDS in B-operand order
+    // codes of K chunk c -> LDS in B-operand order; the first batch of chunk 0 is still in registers
     auto x_quant = [&](int c) {
         const int scc = min(p.SC, p.S - c * p.SC);
         const int npieces = scc * 8 * MP;
         for (int base = 0; base < npieces; base += nthreads * XB) {
             u32x4 v[XB];
+            const bool held = c == 0 && base == 0;
 #pragma unroll
             for (int i = 0; i < XB; ++i) {
                 const int idx = base + i * nthreads + tid;
-                v[i] = u32x4{0u, 0u, 0u, 0u};
-                if (idx < npieces && m_own < p.M)
-                    v[i] = *reinterpret_cast<const u32x4 *>(p.x + m_own * p.ldx + (long long)c * p.SC * kStepK8 +
-                                                            8ll * (idx >> LMP));
+                v[i] = xfirst[i];
+                if (!held) {
+                    v[i] = u32x4{0u, 0u, 0u, 0u};
+                    if (idx < npieces && m_own < p.M)
+                        v[i] = *reinterpret_cast<const u32x4 *>(p.x + m_own * p.ldx + (long long)c * p.SC * kStepK8 +
+                                                                8ll * (idx >> LMP));
+                }
             }
 #pragma unroll
             for (int i = 0; i < XB; ++i) {
