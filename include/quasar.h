@@ -252,6 +252,19 @@ int quasar_w8a8_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int6
                               int32_t *out_argmax, int32_t *out_accept_len,
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The whole-step launch in the W8A8 form: as quasar_sequence_prepare, every linear and the
+ * vocabulary phase computed as quasar_w8a8_linear / quasar_w8a8_lmhead_verify compute them
+ * (same bits).  smooth: host array of n_linears device pointers ([K_i] fp32 each, entries or
+ * the array itself may be NULL); verify_smooth likewise for the vocabulary phase.  Linears
+ * that share their input share a phase only if they also share the smoothing vector.
+ * quasar_sequence_run runs the prepared handle. */
+int quasar_sequence_prepare_w8a8(const quasar_linear_desc *linears, int64_t n_linears,
+                                 const float *const *smooth,
+                                 const quasar_verify_desc *verify /* may be NULL */,
+                                 const float *verify_smooth, int64_t M,
+                                 void *plan_device, size_t plan_bytes,
+                                 void *workspace, size_t workspace_bytes, quasar_sequence *seq);
+
 /*
  * Measurement helpers (the bandwidth term of Eq. 11-12 measured directly).
  * quasar_read_stream reads `bytes` (multiple of 16) from `src` with the same

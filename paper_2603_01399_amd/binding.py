@@ -28,7 +28,7 @@ EXPORTS = (
     "quasar_sequence_plan_bytes", "quasar_sequence_workspace_bytes", "quasar_sequence_prepare",
     "quasar_sequence_run",
     "quasar_quantize_weights_smoothed", "quasar_quantize_activations", "quasar_w8a8_linear",
-    "quasar_w8a8_lmhead_verify",
+    "quasar_w8a8_lmhead_verify", "quasar_sequence_prepare_w8a8",
 )
 
 
@@ -90,6 +90,7 @@ def _load() -> ctypes.CDLL:
     lib.quasar_sequence_workspace_bytes.restype = sz
     lib.quasar_sequence_prepare.argtypes = [vp, i64, vp, i64, vp, sz, vp, sz, vp]
     lib.quasar_sequence_run.argtypes = [vp, vp, vp, sz, vp]
+    lib.quasar_sequence_prepare_w8a8.argtypes = [vp, i64, vp, vp, vp, i64, vp, sz, vp, sz, vp]
     lib.quasar_quantize_weights_smoothed.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.quasar_quantize_activations.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
     lib.quasar_w8a8_linear.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, sz, vp]
@@ -365,10 +366,12 @@ class Sequence:
 
     linears: list of (x, w_packed, scales_or_None, N, y) tensor tuples in execution order;
     verify: optional (hidden, w_packed, scales_or_None, V, draft_ids, out_argmax, out_accept).
+    w8a8=True runs every phase in the W8A8 form; smooth is then an optional list with one
+    [K] fp32 vector (or None) per linear, verify_smooth the one of the vocabulary phase.
     The tensors are only borrowed: the caller keeps them alive.
     """
 
-    def __init__(self, linears, verify=None, M=None):
+    def __init__(self, linears, verify=None, M=None, w8a8=False, smooth=None, verify_smooth=None):
         descs = (LinearDesc * max(len(linears), 1))()
         keep = []
         for i, (x, wp, sc, N, y) in enumerate(linears):
@@ -400,12 +403,35 @@ class Sequence:
         self.workspace = torch.empty(_lib.quasar_sequence_workspace_bytes(len(linears), M), dtype=torch.uint8,
                                      device=dev)
         self.handle = SequenceHandle()
-        _check("quasar_sequence_prepare",
-               _lib.quasar_sequence_prepare(ctypes.cast(descs, ctypes.c_void_p), len(linears),
-                                            None if vdesc is None else ctypes.cast(ctypes.pointer(vdesc), ctypes.c_void_p),
-                                            M, _ptr(self.plan), self.plan.numel(),
-                                            _ptr(self.workspace), self.workspace.numel(),
-                                            ctypes.cast(ctypes.pointer(self.handle), ctypes.c_void_p)))
+        vptr = None if vdesc is None else ctypes.cast(ctypes.pointer(vdesc), ctypes.c_void_p)
+        hptr = ctypes.cast(ctypes.pointer(self.handle), ctypes.c_void_p)
+        if not w8a8:
+            if smooth is not None or verify_smooth is not None:
+                raise ValueError("smoothing vectors belong to the W8A8 form")
+            _check("quasar_sequence_prepare",
+                   _lib.quasar_sequence_prepare(ctypes.cast(descs, ctypes.c_void_p), len(linears), vptr,
+                                                M, _ptr(self.plan), self.plan.numel(),
+                                                _ptr(self.workspace), self.workspace.numel(), hptr))
+            return
+        sm_arr = None
+        if smooth is not None:
+            if len(smooth) != len(linears):
+                raise ValueError("smooth needs one entry per linear")
+            sm_arr = (ctypes.c_void_p * max(len(linears), 1))()
+            for i, (sv, lin) in enumerate(zip(smooth, linears)):
+                if sv is not None:
+                    _smooth_arg(sv, lin[0].shape[1])
+                    sm_arr[i] = sv.data_ptr()
+            keep.append(list(smooth))
+        vsm = None
+        if verify_smooth is not None:
+            vsm = _smooth_arg(verify_smooth, verify[0].shape[1])
+            keep.append(verify_smooth)
+        _check("quasar_sequence_prepare_w8a8",
+               _lib.quasar_sequence_prepare_w8a8(ctypes.cast(descs, ctypes.c_void_p), len(linears),
+                                                 None if sm_arr is None else ctypes.cast(sm_arr, ctypes.c_void_p),
+                                                 vptr, vsm, M, _ptr(self.plan), self.plan.numel(),
+                                                 _ptr(self.workspace), self.workspace.numel(), hptr))
 
     @property
     def nphases(self) -> int:

@@ -412,7 +412,7 @@ constexpr int kSeqMagic = 0x51534551;   // "QSEQ"
 constexpr unsigned int kSeqSpinLimit = 4000000u;
 
 struct SeqHandle {   // lives in quasar_sequence::words
-    int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears, pad;
+    int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears, a8;
     int n_barriers, n_flag_waits;
 };
 static_assert(sizeof(SeqHandle) <= sizeof(quasar_sequence), "handle must fit");
@@ -421,13 +421,15 @@ struct Range { uintptr_t lo, hi; };
 bool overlaps(const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi; }
 
 // Chunking of one phase for a fixed grid; returns false if it cannot fit the LDS.
-bool plan_phase(SeqPhase &ph, int MP, bool w16, int G, int &xs_bytes, int &sc_bytes, int &acc_bytes) {
+bool plan_phase(SeqPhase &ph, int MP, bool w16, bool a8, int G, int &xs_bytes, int &sc_bytes, int &acc_bytes) {
     const int NB = MP == 32 ? 2 : 1;
-    const int x_bytes_per_step = (w16 ? 64 : 128) * MP;
+    // bytes of LDS one step of activations takes: bf16 (64 k per int8 step, 32 per bf16 step) or int8 codes
+    const int x_bytes_per_step = ((w16 || a8) ? 64 : 128) * MP;
     choose_chunks(ph.S, x_bytes_per_step, 2 * kSeqWaves * NB * 1024, ph.SC, ph.C);
     const int tpw = (ph.T + G - 1) / G;
     xs_bytes = ph.SC * x_bytes_per_step;
-    sc_bytes = w16 ? 0 : ((tpw * kTileRows * 2 + 15) / 16) * 16;
+    // row scales, then 256 bytes for the per-token step sizes of the W8A8 form
+    sc_bytes = (w16 ? 0 : ((tpw * kTileRows * 2 + 15) / 16) * 16) + 256;
     acc_bytes = ph.C > 1 ? tpw * NB * 1024 : 0;
     return true;
 }
@@ -451,9 +453,9 @@ int launch_w8a8(const GemmParams &base, int M, hipStream_t stream, int *grid_out
     return launch(stream_w8a8_kernel<32, EPI, 16, 8>, pl.grid, 1024, lds, stream, p);
 }
 
-template <int MP, bool W16>
+template <int MP, bool W16, bool A8>
 int launch_sequence(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
-    auto kernel = stream_sequence_kernel<MP, W16, kSeqWaves, kSeqDepth>;
+    auto kernel = stream_sequence_kernel<MP, W16, A8, kSeqWaves, kSeqDepth>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return QUASAR_ERR_HIP;
     hipLaunchKernelGGL(sequence_reset_kernel, dim3(1), dim3(64), 0, st, sp.sync);
     // Plain launch: one workgroup per compute unit is resident by construction (grid = number
@@ -481,9 +483,10 @@ size_t quasar_sequence_workspace_bytes(int64_t n_linears, int64_t M) {
     return 256 + kSeqPartialBytes + (size_t)(n_linears + 1) * kMaxGrid * sizeof(unsigned int);
 }
 
-int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears, const quasar_verify_desc *verify,
-                            int64_t M, void *plan_device, size_t plan_bytes, void *workspace, size_t workspace_bytes,
-                            quasar_sequence *seq) {
+static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_linears, const float *const *smooth,
+                                 const quasar_verify_desc *verify, const float *verify_smooth, bool a8, int64_t M,
+                                 void *plan_device, size_t plan_bytes, void *workspace, size_t workspace_bytes,
+                                 quasar_sequence *seq) {
     if (!seq || !plan_device || !workspace || (n_linears > 0 && !linears)) return QUASAR_ERR_NULL;
     if (workspace_bytes < quasar_sequence_workspace_bytes(n_linears, M) || !aligned(workspace, 16))
         return QUASAR_ERR_WORKSPACE;
@@ -492,6 +495,7 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
     if (plan_bytes < quasar_sequence_plan_bytes(n_linears)) return QUASAR_ERR_WORKSPACE;
     if (!aligned(plan_device, 16)) return QUASAR_ERR_ALIGN;
     const bool w16 = n_linears > 0 ? linears[0].scales == nullptr : verify->scales == nullptr;
+    if (a8 && w16) return QUASAR_ERR_DTYPE;
     const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
     const int NB = MP == 32 ? 2 : 1;
     const int G = device_cus();
@@ -544,10 +548,14 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
         const Range xr{reinterpret_cast<uintptr_t>(d.x), reinterpret_cast<uintptr_t>(d.x + (M - 1) * d.ldx + d.K)};
         const Range yr{reinterpret_cast<uintptr_t>(d.y), reinterpret_cast<uintptr_t>(d.y + (M - 1) * d.ldy + d.N)};
         if (overlaps(xr, yr)) return QUASAR_ERR_SHAPE;    // in-place is not supported
-        // join the previous phase when it reads the same input and nothing orders the two
+        const float *sm = (a8 && smooth) ? smooth[i] : nullptr;
+        if (!aligned(sm, 16)) return QUASAR_ERR_ALIGN;
+        // join the previous phase when it reads the same input (smoothed the same way) and nothing
+        // orders the two
         if (!phases.empty()) {
             SeqPhase &p = phases.back();
-            if (p.kind == EPI_LINEAR && p.nseg < kMaxSeg && p.x == d.x && p.ldx == d.ldx && p.K == (int)d.K) {
+            if (p.kind == EPI_LINEAR && p.nseg < kMaxSeg && p.x == d.x && p.ldx == d.ldx && p.K == (int)d.K &&
+                p.smooth == sm) {
                 bool clash = false;
                 // (the shared input is already waited for by the phase being joined)
                 for (const Range &wr : writes) if (overlaps(yr, wr)) clash = true;
@@ -566,6 +574,7 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
             }
         }
         SeqPhase p{};
+        p.smooth = sm;
         p.x = d.x; p.ldx = d.ldx; p.nseg = 1; p.K = (int)d.K;
         p.S = (int)(d.K / (w16 ? kStepK16 : kStepK8));
         p.T = (int)(d.N / kTileRows);
@@ -594,7 +603,9 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
         if (const int e = check_mnk(M, v.V, v.K)) return e;
         if (v.V > 0x7FFFFFF0ll || v.n_draft < 0 || v.n_draft > M || v.ldh < v.K || v.ldh % 8) return QUASAR_ERR_SHAPE;
         if (!aligned(v.hidden, 16) || !aligned(v.w_packed, 16) || (!w16 && !aligned(v.scales, 8))) return QUASAR_ERR_ALIGN;
+        if (!aligned(verify_smooth, 16)) return QUASAR_ERR_ALIGN;
         SeqPhase p{};
+        p.smooth = a8 ? verify_smooth : nullptr;
         p.x = v.hidden; p.ldx = v.ldh; p.nseg = 1; p.K = (int)v.K;
         p.S = (int)(v.K / (w16 ? kStepK16 : kStepK8));
         p.T = (int)(v.V / kTileRows);
@@ -617,7 +628,7 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
     int xs_max = 0, sc_max = 0, acc_max = 0;
     for (SeqPhase &p : phases) {
         int xs, sc, ac;
-        plan_phase(p, MP, w16, G, xs, sc, ac);
+        plan_phase(p, MP, w16, a8, G, xs, sc, ac);
         if (xs > xs_max) xs_max = xs;
         if (sc > sc_max) sc_max = sc;
         if (ac > acc_max) acc_max = ac;
@@ -635,7 +646,7 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
     SeqHandle h{};
     h.magic = kSeqMagic; h.nphases = (int)phases.size(); h.M = (int)M; h.MP = MP; h.w16 = w16 ? 1 : 0;
     h.xs_bytes = xs_max; h.sc_bytes = sc_max; h.lds_bytes = lds < kMinLds ? kMinLds : lds; h.grid = G;
-    h.has_verify = verify ? 1 : 0; h.n_linears = (int)n_linears;
+    h.has_verify = verify ? 1 : 0; h.n_linears = (int)n_linears; h.a8 = a8 ? 1 : 0;
     h.n_barriers = 0; h.n_flag_waits = 0;
     for (const SeqPhase &p : phases) {
         if (p.wait == SEQ_WAIT_BARRIER) ++h.n_barriers;
@@ -644,6 +655,21 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
     std::memset(seq, 0, sizeof(*seq));
     std::memcpy(seq, &h, sizeof(h));
     return QUASAR_OK;
+}
+
+int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears, const quasar_verify_desc *verify,
+                            int64_t M, void *plan_device, size_t plan_bytes, void *workspace, size_t workspace_bytes,
+                            quasar_sequence *seq) {
+    return sequence_prepare_impl(linears, n_linears, nullptr, verify, nullptr, false, M, plan_device, plan_bytes,
+                                 workspace, workspace_bytes, seq);
+}
+
+int quasar_sequence_prepare_w8a8(const quasar_linear_desc *linears, int64_t n_linears, const float *const *smooth,
+                                 const quasar_verify_desc *verify, const float *verify_smooth, int64_t M,
+                                 void *plan_device, size_t plan_bytes, void *workspace, size_t workspace_bytes,
+                                 quasar_sequence *seq) {
+    return sequence_prepare_impl(linears, n_linears, smooth, verify, verify_smooth, true, M, plan_device, plan_bytes,
+                                 workspace, workspace_bytes, seq);
 }
 
 int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, void *workspace, size_t workspace_bytes,
@@ -666,13 +692,18 @@ int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, voi
                                                (size_t)(h.n_linears + 1) * sizeof(SeqPhase));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (h.w16) {
-        if (h.MP == 8) return launch_sequence<8, true>(h, sp, st);
-        if (h.MP == 16) return launch_sequence<16, true>(h, sp, st);
-        return launch_sequence<32, true>(h, sp, st);
+        if (h.MP == 8) return launch_sequence<8, true, false>(h, sp, st);
+        if (h.MP == 16) return launch_sequence<16, true, false>(h, sp, st);
+        return launch_sequence<32, true, false>(h, sp, st);
     }
-    if (h.MP == 8) return launch_sequence<8, false>(h, sp, st);
-    if (h.MP == 16) return launch_sequence<16, false>(h, sp, st);
-    return launch_sequence<32, false>(h, sp, st);
+    if (h.a8) {
+        if (h.MP == 8) return launch_sequence<8, false, true>(h, sp, st);
+        if (h.MP == 16) return launch_sequence<16, false, true>(h, sp, st);
+        return launch_sequence<32, false, true>(h, sp, st);
+    }
+    if (h.MP == 8) return launch_sequence<8, false, false>(h, sp, st);
+    if (h.MP == 16) return launch_sequence<16, false, false>(h, sp, st);
+    return launch_sequence<32, false, false>(h, sp, st);
 }
 
 int quasar_quantize_activations(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const float *smooth,

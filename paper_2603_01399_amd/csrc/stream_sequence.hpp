@@ -19,7 +19,7 @@
 // phases while the workgroup waits for activations.
 #pragma once
 
-#include "stream_gemm.hpp"
+#include "stream_w8a8.hpp"
 
 namespace quasar {
 
@@ -59,6 +59,8 @@ struct SeqPhase {
     int producer[2];         // SEQ_WAIT_FLAGS: phases whose completion flags gate this input (-1: unused)
     int publish;             // a later phase waits for this phase's flags
     int pad_;
+    const float *smooth;     // W8A8: per-channel smoothing factors of the input ([K], nullptr: none)
+    long long pad2_;
 };
 
 typedef const __attribute__((address_space(4))) SeqPhase *const_phase_ptr;   // scalar (constant) loads
@@ -148,11 +150,15 @@ __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int ta
 #define QUASAR_SEQ_XB 8
 #endif
 
-template <int MP, bool W16, int NW, int D>
+// A8 selects the W8A8 form of the linears: the activations are smoothed and quantised per
+// token while they are staged (same arithmetic as stream_w8a8.hpp), the weight step goes
+// straight into the int8 matrix core, the cross-wave sums are exact integers.
+template <int MP, bool W16, bool A8, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParams sp) {
     extern __shared__ __align__(16) unsigned char lds[];
+    static_assert(!(W16 && A8), "the W8A8 form needs int8 weights");
     constexpr int NB = (MP == 32) ? 2 : 1;
-    constexpr int PPS = W16 ? 4 : 8;
+    constexpr int PPS = (W16 || A8) ? 4 : 8;   // 16-byte LDS pieces per step and token
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
     constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
     constexpr int XB = QUASAR_SEQ_XB;
@@ -170,6 +176,9 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
 
     u32x4 *xs = reinterpret_cast<u32x4 *>(lds);
     uint16_t *sc_lds = reinterpret_cast<uint16_t *>(lds + sp.xs_bytes);
+    // the last 256 bytes of the scale region: per-token step sizes and maxima of the W8A8 form
+    float *tok_dx = reinterpret_cast<float *>(lds + sp.xs_bytes + sp.sc_bytes - 256);                  // [32]
+    unsigned int *tok_amax = reinterpret_cast<unsigned int *>(lds + sp.xs_bytes + sp.sc_bytes - 128);  // [32]
     f32x4 *stage = reinterpret_cast<f32x4 *>(lds + sp.xs_bytes + sp.sc_bytes);   // [2][NW][NB][64]
     f32x4 *accs = stage + 2 * NW * NB * 64;                                      // [ntiles][NB][64] (C > 1)
 
@@ -287,17 +296,19 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     unsigned int barriers_done = 0;
     int parity = 0;
     f32x4 acc[NB];
+    i32x4 acci[NB];          // W8A8: exact integer sums
     float bestv[NB];
     unsigned int besti[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acci[nb] = i32x4{0, 0, 0, 0};
         bestv[nb] = -__builtin_inff();
         besti[nb] = 0x7FFFFFFFu;
     }
     const int xm = (MP == 8) ? (mcol & 7) : mcol;
     // this lane's B operand inside a step: 8-element piece (W16: g, else 2g and 2g + 1), token xm
-    const unsigned int xlane = (unsigned int)(((W16 ? g : 2 * g) * MP + xm) * 16);
+    const unsigned int xlane = (unsigned int)((((W16 || A8) ? g : 2 * g) * MP + xm) * 16);
 
     // stage one activation chunk.  `coherent` reads go past the L2 (needed when the buffer may
     // have been cached before it was last written: barrier-ordered, reused buffers); otherwise
@@ -324,6 +335,91 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             for (int i = 0; i < XB; ++i) {
                 const int idx = base + i * nthreads + tid;
                 if (idx < npieces) xs[idx] = v[i];
+            }
+        }
+    };
+    // ---- W8A8 staging (arithmetic of stream_w8a8.hpp).  Every thread always sees the same
+    // token, tid % MP.  The activations are read twice (maxima, then codes); the second read
+    // hits the caches.
+    const int m_own = tid & (MP - 1);
+    float a8_inv = 0.f;
+    constexpr int AXB = 4;       // pieces per thread and batch (= all of x at K = 4096, M <= 8)
+    auto a8_load = [&](const auto &P, long long k, bool coherent) -> u32x4 {
+        if (coherent) return coherent_load_u32x4(P.x + m_own * P.ldx + k);
+        return *as_global(reinterpret_cast<const u32x4 *>(P.x + m_own * P.ldx + k));
+    };
+    auto a8_smooth = [&](const auto &P, const u32x4 &v, long long k, float (&xt)[8]) {
+        const float *sm = P.smooth;
+        if (sm) {
+            const f32x4 s0 = *as_global(reinterpret_cast<const f32x4 *>(sm + k));
+            const f32x4 s1 = *as_global(reinterpret_cast<const f32x4 *>(sm + k + 4));
+            const float sv[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+            smooth_piece(v, nullptr, k, xt);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) xt[j] = xt[j] * sv[j];
+        } else {
+            smooth_piece(v, nullptr, k, xt);
+        }
+    };
+    // per-token maxima over the whole K, then step size and its reciprocal
+    auto x_scan = [&](const auto &P, bool coherent) {
+        if (tid < 32) tok_amax[tid] = 0u;
+        lds_barrier();
+        const int npieces = (P.K / 8) * MP;
+        if (m_own < M) {
+            float amax = 0.f;
+            for (int base = 0; base < npieces; base += nthreads * AXB) {
+                u32x4 v[AXB];
+#pragma unroll
+                for (int i = 0; i < AXB; ++i) {
+                    const int idx = base + i * nthreads + tid;
+                    v[i] = u32x4{0u, 0u, 0u, 0u};
+                    if (idx < npieces) v[i] = a8_load(P, 8ll * (idx >> LMP), coherent);
+                }
+#pragma unroll
+                for (int i = 0; i < AXB; ++i) {
+                    const int idx = base + i * nthreads + tid;
+                    if (idx < npieces) {
+                        float xt[8];
+                        a8_smooth(P, v[i], 8ll * (idx >> LMP), xt);
+                        amax = fmaxf(amax, piece_amax(xt));
+                    }
+                }
+            }
+            __hip_atomic_fetch_max(&tok_amax[m_own], __float_as_uint(amax), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        lds_barrier();
+        const float amax_own = __uint_as_float(tok_amax[m_own]);
+        a8_inv = inverse_step_of(amax_own);
+        if (tid < MP) tok_dx[tid] = step_of(amax_own);
+    };
+    // codes of K chunk c -> LDS in B-operand order [k/16][token][16 B]
+    auto x_quant = [&](const auto &P, int c, bool coherent) {
+        const int scc = min(P.SC, P.S - c * P.SC);
+        const int npieces = scc * 8 * MP;
+        const long long k0 = (long long)c * P.SC * kStepK8;
+        for (int base = 0; base < npieces; base += nthreads * AXB) {
+            u32x4 v[AXB];
+#pragma unroll
+            for (int i = 0; i < AXB; ++i) {
+                const int idx = base + i * nthreads + tid;
+                v[i] = u32x4{0u, 0u, 0u, 0u};
+                if (idx < npieces && m_own < M) v[i] = a8_load(P, k0 + 8ll * (idx >> LMP), coherent);
+            }
+#pragma unroll
+            for (int i = 0; i < AXB; ++i) {
+                const int idx = base + i * nthreads + tid;
+                if (idx < npieces) {
+                    const int p8 = idx >> LMP;
+                    u32x2 codes = {0u, 0u};
+                    if (m_own < M) {
+                        float xt[8];
+                        a8_smooth(P, v[i], k0 + 8ll * p8, xt);
+                        codes = quantize_piece(xt, a8_inv);
+                    }
+                    *reinterpret_cast<u32x2 *>(lds + (((p8 >> 1) * MP + m_own) * 16 + 8 * (p8 & 1))) = codes;
+                }
             }
         }
     };
@@ -479,6 +575,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     continue;
                 }
                 scale_stage(P, c_t0, c_ntiles);
+                if constexpr (A8) x_scan(P, P.wait == SEQ_WAIT_BARRIER);
             }
             const int scc = min(P.SC, P.S - c_c * P.SC);
             const int s_lo = (scc * w) / NW;
@@ -493,7 +590,8 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             nocomp = false;
             c_reseg();
             QUASAR_TRACE(1)
-            x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
+            if constexpr (A8) x_quant(P, c_c, P.wait == SEQ_WAIT_BARRIER);
+            else x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
             QUASAR_TRACE(2)
             // known-empty load queue: keeps the counted waits of the ring exact (see stream_gemm.hpp)
             __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -524,7 +622,9 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             const unsigned char *xp = xsb + (xlane + c_xoff);
             const unsigned long long la = l_base;
             bf16x8 a0, a1;
-            if constexpr (!W16) {
+            if constexpr (A8) {
+                ring[d] = ring_refill_at(la, voff, wv);
+            } else if constexpr (!W16) {
                 a0 = codes_to_bf16x8(wv.x, wv.y);
                 a1 = codes_to_bf16x8(wv.z, wv.w);
                 ring[d] = ring_refill_at(la, voff, wv);
@@ -536,10 +636,15 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     const u32x4 b0 = *reinterpret_cast<const u32x4 *>(xp + nb * 256);
-                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb], 0, 0, 0);
-                    if constexpr (!W16) {
-                        const u32x4 b1 = *reinterpret_cast<const u32x4 *>(xp + nb * 256 + MP * 16);
-                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1), acc[nb], 0, 0, 0);
+                    if constexpr (A8) {
+                        acci[nb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, wv),
+                                                                         __builtin_bit_cast(i32x4, b0), acci[nb], 0, 0, 0);
+                    } else {
+                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb], 0, 0, 0);
+                        if constexpr (!W16) {
+                            const u32x4 b1 = *reinterpret_cast<const u32x4 *>(xp + nb * 256 + MP * 16);
+                            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1), acc[nb], 0, 0, 0);
+                        }
                     }
                 }
             }
@@ -548,26 +653,32 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             if (__builtin_expect(--l_left == 0, 0)) l_event();
             QUASAR_TRACE_SLOT(4)
             if (!nocomp && __builtin_expect(--c_left == 0, 0)) {
-                // ---- tile end: cross-wave sum through LDS, fixed order
-                f32x4 *st = stage + (parity * NW) * NB * 64;
+                // ---- tile end: cross-wave sum through LDS, fixed order (W8A8: exact integers)
+                using acc_t = std::conditional_t<A8, i32x4, f32x4>;
+                acc_t *st = reinterpret_cast<acc_t *>(stage) + (parity * NW) * NB * 64;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    st[(w * NB + nb) * 64 + lane] = acc[nb];
-                    acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if constexpr (A8) {
+                        st[(w * NB + nb) * 64 + lane] = acci[nb];
+                        acci[nb] = i32x4{0, 0, 0, 0};
+                    } else {
+                        st[(w * NB + nb) * 64 + lane] = acc[nb];
+                        acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
                 }
                 lds_barrier();
                 // the epilogue rotates over waves 1..NW-1: wave 0 polls for the next phase's input
                 // and should never have to wait for its own stores
                 if (w == 1 + (c_tl % (NW - 1))) {
                     stored = true;
-                    f32x4 rsum[NB];
+                    acc_t rsum[NB];
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
                         rsum[nb] = st[nb * 64 + lane];
 #pragma unroll
                         for (int ww = 1; ww < NW; ++ww) rsum[nb] += st[(ww * NB + nb) * 64 + lane];
                         if (c_C > 1) {
-                            f32x4 *a = accs + (c_tl * NB + nb) * 64 + lane;
+                            acc_t *a = reinterpret_cast<acc_t *>(accs) + (c_tl * NB + nb) * 64 + lane;
                             if (c_c > 0) rsum[nb] += *a;
                             if (c_c < c_C - 1) *a = rsum[nb];
                         }
@@ -585,8 +696,20 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
 #pragma unroll
                         for (int nb = 0; nb < NB; ++nb) {
                             const int m = mcol + 16 * nb;
-                            const float v0 = rsum[nb].x * s4[0], v1 = rsum[nb].y * s4[1];
-                            const float v2 = rsum[nb].z * s4[2], v3 = rsum[nb].w * s4[3];
+                            float v0, v1, v2, v3;
+                            if constexpr (A8) {
+                                // Eq. 10: fp32(acc) * (dx * dw), each one fp32 operation
+                                const float dxm = tok_dx[m];
+                                v0 = (float)rsum[nb].x * (dxm * s4[0]);
+                                v1 = (float)rsum[nb].y * (dxm * s4[1]);
+                                v2 = (float)rsum[nb].z * (dxm * s4[2]);
+                                v3 = (float)rsum[nb].w * (dxm * s4[3]);
+                            } else {
+                                v0 = rsum[nb].x * s4[0];
+                                v1 = rsum[nb].y * s4[1];
+                                v2 = rsum[nb].z * s4[2];
+                                v3 = rsum[nb].w * s4[3];
+                            }
                             if (c_kind == EPI_LINEAR) {
                                 if (m < M) {
                                     const unsigned long long lo =

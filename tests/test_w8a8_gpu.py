@@ -216,3 +216,100 @@ def test_w8a8_argument_errors(qb):
     small = torch.empty(16, dtype=torch.uint8, device="cuda")
     with pytest.raises(qb.QuasarError):
         qb.w8a8_lmhead_verify(x, wq, sc, 16, None, small)  # workspace too small
+
+
+# ------------------------------------------------------------------ whole step in one launch, W8A8 form
+def _chain_case(qb, M, dims, seed, smoothed, with_head, V=2048):
+    """A chain of linears (each reads its predecessor's output; the two middle ones share
+    their input, as q|k or gate|up do), optionally closed by the vocabulary phase."""
+    r = np.random.Generator(np.random.Philox(seed))
+    xb0 = activations(M, dims[0], synth.seed_for(6, 7, seed))
+    layers = []                                   # (K, N, q_ref, d_ref, wq, sc, smooth_host, smooth_dev, src)
+    src = -1                                      # -1: the external input
+    for i in range(len(dims) - 1):
+        K, N = dims[i], dims[i + 1]
+        for rep in range(2 if i == 1 else 1):     # second stage: two linears on the same input
+            w = synth.normal_weights(N, K, seed=synth.seed_for(6, 8, 10 * seed + 2 * i + rep)) * np.float32(4.0)
+            s = smooth_vector(K, 300 + seed + i) if smoothed else None
+            wt = a8.smooth_weights(w, s) if smoothed else w
+            q_ref, d_ref = ref.quantize_weights(wt)
+            s_dev = None if s is None else f32_to_dev(s)
+            wq, sc = qb.quantize_weights_smoothed(f32_to_dev(w), s_dev)
+            layers.append([K, N, q_ref, d_ref, wq, sc, s, s_dev, src])
+        src = len(layers) - 1                     # the next stage reads the last linear of this one
+    head = None
+    if with_head:
+        K = dims[-1]
+        w = synth.normal_weights(V, K, seed=synth.seed_for(6, 9, seed))
+        s = smooth_vector(K, 400 + seed) if smoothed else None
+        q_ref, d_ref = ref.quantize_weights(a8.smooth_weights(w, s) if smoothed else w)
+        s_dev = None if s is None else f32_to_dev(s)
+        wq, sc = qb.quantize_weights_smoothed(f32_to_dev(w), s_dev)
+        head = (V, q_ref, d_ref, wq, sc, s, s_dev)
+    return xb0, layers, head
+
+
+@pytest.mark.parametrize("M,dims,seed,smoothed,with_head", [
+    (8, (1024, 1024, 512, 1024), 1, False, False),
+    (8, (4096, 4096, 1024, 4096), 2, True, True),
+    (5, (192, 256, 64, 128), 3, True, True),          # fewer steps than waves, ragged M
+    (16, (2048, 12288, 1024, 2048), 4, False, True),  # long K in the third stage
+    (32, (8192, 512, 8192, 256), 5, True, False),     # K chunked in LDS
+])
+def test_w8a8_sequence_bit_exact(qb, M, dims, seed, smoothed, with_head):
+    say("w8a8 sequence", M, dims, seed, smoothed, with_head)
+    xb0, layers, head = _chain_case(qb, M, dims, seed, smoothed, with_head)
+    # oracle chain
+    outs_ref = []
+    for K, N, q_ref, d_ref, wq, sc, s, s_dev, src in layers:
+        xin = xb0 if src < 0 else outs_ref[src]
+        outs_ref.append(a8.w8a8_linear(xin, q_ref, d_ref, s))
+    # device chain in one launch; every buffer written once
+    x0 = bf16_to_dev(xb0)
+    ys = [torch.empty((M, L[1]), dtype=torch.bfloat16, device="cuda") for L in layers]
+    lin = [(x0 if L[8] < 0 else ys[L[8]], L[4], L[5], L[1], ys[i]) for i, L in enumerate(layers)]
+    verify = None
+    draft = None
+    if head is not None:
+        V, q_ref, d_ref, wq, sc, s, s_dev = head
+        want, _ = a8.w8a8_lmhead_verify(outs_ref[-1], q_ref, d_ref, [], s)
+        draft = want[:M - 1].copy()
+        j = (M - 1) // 2
+        draft[j] = (draft[j] + 1) % V
+        oa = torch.empty(M, dtype=torch.int32, device="cuda")
+        oc = torch.empty(1, dtype=torch.int32, device="cuda")
+        verify = (ys[-1], wq, sc, V, i32_to_dev(draft), oa, oc)
+    seq = qb.Sequence(lin, verify=verify, w8a8=True, smooth=[L[7] for L in layers] if smoothed else None,
+                      verify_smooth=head[6] if head is not None else None)
+    assert seq.n_barriers == 0
+    for _ in range(2):                             # the second run reuses flags of a new epoch
+        for y in ys:
+            y.fill_(float("nan"))
+        seq.run()
+        torch.cuda.synchronize()
+        assert not seq.timed_out()
+        for i, y in enumerate(ys):
+            assert np.array_equal(bf16_to_host(y), outs_ref[i]), i
+        if head is not None:
+            assert np.array_equal(oa.cpu().numpy(), want)
+            assert int(oc.cpu()[0]) == j
+    # the same bits as the single calls
+    for i, L in enumerate(layers):
+        xin = x0 if L[8] < 0 else ys[L[8]]
+        y1 = qb.w8a8_linear(xin, L[4], L[5], L[1], smooth=L[7])
+        assert torch.equal(y1.view(torch.int16), ys[i].view(torch.int16))
+
+
+def test_w8a8_sequence_argument_errors(qb):
+    say("w8a8 sequence argument errors")
+    x = torch.zeros((8, 128), dtype=torch.bfloat16, device="cuda")
+    y = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda")
+    wq = torch.zeros(64 * 128, dtype=torch.int8, device="cuda")
+    sc = torch.zeros(64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ValueError):
+        qb.Sequence([(x, wq, sc, 64, y)], w8a8=True, smooth=[None, None])
+    with pytest.raises(ValueError):
+        qb.Sequence([(x, wq, sc, 64, y)], smooth=[None])
+    wp = torch.zeros(64 * 128, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(qb.QuasarError):
+        qb.Sequence([(x, wp, None, 64, y)], w8a8=True)      # bf16 weights have no W8A8 form
