@@ -38,6 +38,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=None, help="override the layer count (debug only)")
     ap.add_argument("--detail", action="store_true", help="also time every linear shape cold, the bf16 twin step "
                     "and the pure read stream (stderr)")
+    ap.add_argument("--detail32", action="store_true", help="also time the Qwen3-32B layer shapes cold at "
+                    "M = 8, 16, 32 (both forms of the linear)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true", help="also run the plain copy kernel over 1 GiB (reference "
                     "for scaling hardware byte counters in rocprofv3 --pmc runs)")
@@ -364,6 +366,41 @@ def main() -> int:
         torch.cuda.synchronize()
         nb = sum(lin[4][3].numel() for lin in layers) + head_q.numel()
         log(f"  pure read stream over gate_proj copies + LM head: {nb / (e0.elapsed_time(e1) * 1e3) / 1e3:.1f} GB/s")
+
+    if args.detail32:
+        # the larger model's layer shapes, cold: consecutive launches walk through >= 1.2 GB of distinct copies
+        for name, K, N in synth.QWEN3_32B_LAYER:
+            ncopy = min(36, max(4, -(-1_200_000_000 // (N * K))))
+            copies = []
+            for c in range(ncopy):
+                gen.manual_seed(synth.seed_for(5, c, len(copies)))
+                w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+                copies.append(qb.quantize_weights(w))
+                del w
+            for Mv in (8, 16, 32):
+                x = torch.randn((Mv, K), device=dev).to(torch.bfloat16)
+                y = torch.empty((Mv, N), dtype=torch.bfloat16, device=dev)
+                wsk = qb.make_workspace(Mv, N, K)
+                for label, fn in (("w8", lambda wq, sc: qb.w8_linear(x, wq, sc, N, y)),
+                                  ("w8+ws", lambda wq, sc: qb.w8_linear(x, wq, sc, N, y, wsk)),
+                                  ("w8a8", lambda wq, sc: qb.w8a8_linear(x, wq, sc, N, y=y))):
+                    for wq, sc in copies:
+                        fn(wq, sc)
+                    torch.cuda.synchronize()
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(3):
+                        for wq, sc in copies:
+                            fn(wq, sc)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    us = e0.elapsed_time(e1) * 1e3 / (3 * ncopy)
+                    nb = N * K + 2 * N + 2 * Mv * K + 2 * Mv * N
+                    log(f"  32B cold {label:5s} {name:10s} {K:6d}->{N:6d} M={Mv:2d}: {us:7.2f} us  {nb / us / 1e3:7.1f} GB/s "
+                        f"({nb / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
+                    detail[f"q32b_{label}_{name}_M{Mv}_us"] = us
+            del copies
 
     # ------------------------------------------------------------- CPU oracle on the host cores
     cpu = None

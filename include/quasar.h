@@ -71,8 +71,12 @@ int quasar_get_path(void);
 size_t quasar_packed_bytes(int64_t N, int64_t K);
 size_t quasar_packed_bytes_bf16(int64_t N, int64_t K);
 
-/* Workspace bytes needed by quasar_*_lmhead_verify (per-workgroup argmax
- * partials); the linear entry points need none today and accept NULL. */
+/* Workspace bytes for quasar_*_lmhead_verify (per-workgroup argmax partials, always needed
+ * there) and for the linear entry points.  A linear works without a workspace (NULL); given
+ * one of at least this size, shapes whose activations do not fit the on-chip memory in one
+ * piece (large M x K) split K across workgroups through fp32 partial sums in the workspace
+ * instead of re-reading the activations chunk by chunk - same result up to fp32 summation
+ * order, several times faster.  The workspace is scratch: undefined on entry and on exit. */
 size_t quasar_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
@@ -98,7 +102,7 @@ int quasar_unpack_weights(const int8_t *wq_packed, int64_t N, int64_t K,
  *     y[m, n] = bf16( ( sum_k x[m, k] * q[n, k] ) * delta_n ),  fp32 accumulation.
  *   x  device [M, K] bf16, row stride ldx        y  device out [M, N] bf16, row stride ldy
  *   wq_packed / scales_bf16 as produced by quasar_quantize_weights
- *   workspace may be NULL (unused today).
+ *   workspace may be NULL; see quasar_workspace_bytes for what a workspace buys.
  * Weight bytes are read from HBM exactly once (the 1-byte-per-parameter term of
  * Eq. 12).
  */

@@ -321,15 +321,17 @@ def pack_bf16_weights(w: torch.Tensor, w_packed: torch.Tensor = None) -> torch.T
     return w_packed
 
 
-def bf16_linear(x: torch.Tensor, w_packed: torch.Tensor, N: int, y: torch.Tensor = None) -> torch.Tensor:
+def bf16_linear(x: torch.Tensor, w_packed: torch.Tensor, N: int, y: torch.Tensor = None,
+                workspace: torch.Tensor = None) -> torch.Tensor:
     _dev(x, "x", torch.bfloat16)
     _dev(w_packed, "w_packed", torch.bfloat16)
     M, K = x.shape
     if y is None:
         y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check("quasar_bf16_linear",
            _lib.quasar_bf16_linear(_ptr(x), M, K, x.stride(0), _ptr(w_packed), N, _ptr(y), y.stride(0),
-                                   None, 0, _stream()))
+                                   _ptr(workspace), ws_bytes, _stream()))
     return y
 
 

@@ -96,13 +96,13 @@ void choose_chunks(int S, int x_bytes_per_step, int stage_bytes, int &SC, int &C
 
 // x_bytes_per_step: LDS bytes one step of activations occupies; unit_bytes: LDS bytes of one
 // tile accumulator / staging slot per wave; with_scales: reserve the row-scale table.
-Plan make_plan(int T, int S, int x_bytes_per_step, int unit_bytes, int NW, bool with_scales) {
+Plan make_plan(int T, int S, int x_bytes_per_step, int unit_bytes, int NW, bool with_scales, int grid_want = 0) {
     Plan pl{};
     pl.S = S;
     choose_chunks(S, x_bytes_per_step, 2 * NW * unit_bytes, pl.SC, pl.C);
     pl.xs_bytes = pl.SC * x_bytes_per_step;
     const int stage = 2 * NW * unit_bytes;
-    int grid = device_cus() * g_tune_wgs.load();
+    int grid = grid_want > 0 ? grid_want : device_cus() * g_tune_wgs.load();
     if (grid > T) grid = T;
     // tiles per workgroup are bounded by the LDS left for the scale table and, when K is
     // chunked, the per-tile running sums
@@ -147,33 +147,86 @@ int launch(KernelT kernel, int grid, int block, int lds_bytes, hipStream_t strea
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
+// K split across workgroups for the bf16-activation linear: how many slices (1 = no split) and
+// steps per slice, such that the activations of one slice fit the LDS in one piece.
+void splitk_shape(int M, int S, bool w16, int &ksplit, int &slice_steps) {
+    const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
+    const int NB = MP == 32 ? 2 : 1;
+    const int xbps = (w16 ? 64 : 128) * MP;
+    int SC = 0, C = 0;
+    choose_chunks(S, xbps, 2 * 16 * NB * 1024, SC, C);
+    ksplit = 1;
+    slice_steps = S;
+    if (C <= 1) return;
+    int single = kMaxLds - 2 * 16 * NB * 1024 - 8 * 1024;
+    if (single > kSingleChunkX) single = kSingleChunkX;
+    int per = single / xbps;
+    if (per < 1) per = 1;
+    ksplit = (S + per - 1) / per;
+    slice_steps = (S + ksplit - 1) / ksplit;          // equal slices ...
+    // ... in whole multiples of 16 steps where that is possible: the 16 waves of a workgroup share
+    // a slice's steps, and a ragged share leaves some of them idle at every tile
+    const int up = (slice_steps + 15) / 16 * 16;
+    if (up <= per) slice_steps = up;
+    else if (MP < 32 && slice_steps >= 16) slice_steps -= slice_steps % 16;
+    ksplit = (S + slice_steps - 1) / slice_steps;
+}
+size_t splitk_bytes(int M, int N, int ksplit) { return ksplit > 1 ? (size_t)ksplit * M * N * sizeof(float) : 0; }
+
 template <bool W16, int EPI>
-int launch_mfma(const GemmParams &base, int M, hipStream_t stream, int *grid_out) {
+int launch_mfma(const GemmParams &base, int M, hipStream_t stream, int *grid_out, void *workspace = nullptr,
+                size_t workspace_bytes = 0) {
     GemmParams p = base;
+    p.Srow = p.S;
+    p.ksplit = 1;
     const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
     const int NB = MP == 32 ? 2 : 1;
     const int NW = g_tune_nw.load();
-    const Plan pl = make_plan(p.T, p.S, (W16 ? 64 : 128) * MP, NB * 1024, NW, !W16);
-    if (pl.grid > kMaxGrid) return QUASAR_ERR_SHAPE;
+    Plan pl = make_plan(p.T, p.S, (W16 ? 64 : 128) * MP, NB * 1024, NW, !W16);
+    int launch_grid = pl.grid;
+    if (EPI == EPI_LINEAR && pl.C > 1 && NW == 16 && workspace && aligned(workspace, 16)) {
+        int ksplit = 1, slice_steps = p.S;
+        splitk_shape(M, p.S, W16, ksplit, slice_steps);
+        const int groups = device_cus() / ksplit;
+        if (ksplit > 1 && groups >= 1 && workspace_bytes >= splitk_bytes(M, p.N, ksplit)) {
+            const Plan ps = make_plan(p.T, slice_steps, (W16 ? 64 : 128) * MP, NB * 1024, NW, !W16, groups);
+            if (ps.C == 1 && (long long)ps.grid * ksplit <= kMaxGrid) {
+                pl = ps;
+                p.ksplit = ksplit;
+                p.slice_steps = slice_steps;
+                p.part32 = static_cast<float *>(workspace);
+                launch_grid = ps.grid * ksplit;
+            }
+        }
+    }
+    if (launch_grid > kMaxGrid) return QUASAR_ERR_SHAPE;
     p.SC = pl.SC;
     p.C = pl.C;
     p.xs_bytes = pl.xs_bytes;
     p.sc_bytes = pl.sc_bytes;
-    if (grid_out) *grid_out = pl.grid;
+    if (grid_out) *grid_out = launch_grid;
     const int DD = g_tune_d.load();
 #define QUASAR_LAUNCH(MPV)                                                                                   \
-    (NW == 16 ? (DD == 8 ? launch(stream_mfma_kernel<MPV, W16, EPI, 16, 8>, pl.grid, 1024, pl.lds_bytes, stream, p) \
-                         : launch(stream_mfma_kernel<MPV, W16, EPI, 16, 4>, pl.grid, 1024, pl.lds_bytes, stream, p)) \
-              : (DD == 8 ? launch(stream_mfma_kernel<MPV, W16, EPI, 8, 8>, pl.grid, 512, pl.lds_bytes, stream, p)    \
-                         : launch(stream_mfma_kernel<MPV, W16, EPI, 8, 4>, pl.grid, 512, pl.lds_bytes, stream, p)))
-    if (MP == 8) return QUASAR_LAUNCH(8);
-    if (MP == 16) return QUASAR_LAUNCH(16);
-    return QUASAR_LAUNCH(32);
+    (NW == 16 ? (DD == 8 ? launch(stream_mfma_kernel<MPV, W16, EPI, 16, 8>, launch_grid, 1024, pl.lds_bytes, stream, p) \
+                         : launch(stream_mfma_kernel<MPV, W16, EPI, 16, 4>, launch_grid, 1024, pl.lds_bytes, stream, p)) \
+              : (DD == 8 ? launch(stream_mfma_kernel<MPV, W16, EPI, 8, 8>, launch_grid, 512, pl.lds_bytes, stream, p)    \
+                         : launch(stream_mfma_kernel<MPV, W16, EPI, 8, 4>, launch_grid, 512, pl.lds_bytes, stream, p)))
+    int rc;
+    if (MP == 8) rc = QUASAR_LAUNCH(8);
+    else if (MP == 16) rc = QUASAR_LAUNCH(16);
+    else rc = QUASAR_LAUNCH(32);
 #undef QUASAR_LAUNCH
+    if (rc != QUASAR_OK || p.ksplit == 1) return rc;
+    const long long quads = (long long)M * (p.N / 4);
+    hipLaunchKernelGGL(splitk_finalize_kernel<W16>, dim3((unsigned int)((quads + 255) / 256)), dim3(256), 0, stream,
+                       p.part32, p.ksplit, M, p.N, p.scales, p.y, p.ldy);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
 int launch_valu(const GemmParams &base, int M, hipStream_t stream) {
     GemmParams p = base;
+    p.Srow = p.S;
+    p.ksplit = 1;
     const int MV = M <= 1 ? 1 : (M <= 2 ? 2 : 4);
     const int NW = 8;
     const Plan pl = make_plan(p.T, p.S, MV * kStepK8 * 4, MV * 64, NW, true);
@@ -188,7 +241,7 @@ int launch_valu(const GemmParams &base, int M, hipStream_t stream) {
 
 template <bool W16>
 int linear_impl(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const void *wp, const uint16_t *scales,
-                int64_t N, uint16_t *y, int64_t ldy, void *stream) {
+                int64_t N, uint16_t *y, int64_t ldy, void *workspace, size_t workspace_bytes, void *stream) {
     if (!x || !wp || !y || (!W16 && !scales)) return QUASAR_ERR_NULL;
     if (const int e = check_mnk(M, N, K)) return e;
     if (ldx < K || ldy < N || ldx % 8 || ldy % 8) return QUASAR_ERR_SHAPE;
@@ -202,7 +255,8 @@ int linear_impl(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const void
     p.S = (int)(K / (W16 ? kStepK16 : kStepK8));
     const int path = g_path.load();
     if (!W16 && M <= 4 && path == QUASAR_PATH_VALU) return launch_valu(p, (int)M, static_cast<hipStream_t>(stream));
-    return launch_mfma<W16, EPI_LINEAR>(p, (int)M, static_cast<hipStream_t>(stream), nullptr);
+    return launch_mfma<W16, EPI_LINEAR>(p, (int)M, static_cast<hipStream_t>(stream), nullptr, workspace,
+                                        workspace_bytes);
 }
 
 template <bool W16>
@@ -280,7 +334,15 @@ size_t quasar_packed_bytes_bf16(int64_t N, int64_t K) {
 }
 size_t quasar_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     if (check_mnk(M, N, K)) return 0;
-    return (size_t)kMaxGrid * 32u * sizeof(unsigned long long);
+    size_t need = (size_t)kMaxGrid * 32u * sizeof(unsigned long long);    // argmax partials
+    // fp32 partial sums when K is split across workgroups (int8 or bf16 weights, whichever needs more)
+    for (int w16 = 0; w16 < 2; ++w16) {
+        int ksplit = 1, slice_steps = 0;
+        splitk_shape((int)M, (int)(K / (w16 ? kStepK16 : kStepK8)), w16 != 0, ksplit, slice_steps);
+        const size_t sk = splitk_bytes((int)M, (int)N, ksplit);
+        if (sk > need) need = sk;
+    }
+    return need;
 }
 
 int quasar_quantize_weights_smoothed(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw,
@@ -323,8 +385,7 @@ int quasar_unpack_weights(const int8_t *wq_packed, int64_t N, int64_t K, int8_t 
 int quasar_w8_linear(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const int8_t *wq_packed,
                      const uint16_t *scales_bf16, int64_t N, uint16_t *y, int64_t ldy, void *workspace,
                      size_t workspace_bytes, void *hip_stream) {
-    (void)workspace; (void)workspace_bytes;
-    return linear_impl<false>(x, M, K, ldx, wq_packed, scales_bf16, N, y, ldy, hip_stream);
+    return linear_impl<false>(x, M, K, ldx, wq_packed, scales_bf16, N, y, ldy, workspace, workspace_bytes, hip_stream);
 }
 
 int quasar_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh, const int8_t *wq_packed,
@@ -356,8 +417,7 @@ int quasar_pack_bf16_weights(const void *w, int w_dtype, int64_t N, int64_t K, i
 
 int quasar_bf16_linear(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const uint16_t *w_packed, int64_t N,
                        uint16_t *y, int64_t ldy, void *workspace, size_t workspace_bytes, void *hip_stream) {
-    (void)workspace; (void)workspace_bytes;
-    return linear_impl<true>(x, M, K, ldx, w_packed, nullptr, N, y, ldy, hip_stream);
+    return linear_impl<true>(x, M, K, ldx, w_packed, nullptr, N, y, ldy, workspace, workspace_bytes, hip_stream);
 }
 
 int quasar_bf16_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh, const uint16_t *w_packed,
@@ -437,6 +497,8 @@ bool plan_phase(SeqPhase &ph, int MP, bool w16, bool a8, int G, int &xs_bytes, i
 template <int EPI>
 int launch_w8a8(const GemmParams &base, int M, hipStream_t stream, int *grid_out) {
     GemmParams p = base;
+    p.Srow = p.S;
+    p.ksplit = 1;
     const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
     const int NB = MP == 32 ? 2 : 1;
     // int8 codes: 64 bytes of LDS per token and step; 256 bytes more for the per-token steps

@@ -30,6 +30,12 @@ struct GemmParams {
     int xs_bytes;   // LDS bytes reserved for the activation chunk
     int sc_bytes;   // LDS bytes reserved for the workgroup's row scales
     const float *smooth;   // [K] per-channel smoothing factors of the W8A8 path (nullptr: none)
+    int Srow;       // steps per tile in memory (= S unless the workgroup works on a K slice)
+    // K split across workgroups (bf16-activation linear only): workgroup b works on K slice
+    // b % ksplit of tile group b / ksplit and writes fp32 partial sums, part32[slice][m][n]
+    int ksplit;
+    int slice_steps;
+    float *part32;
 };
 
 enum { EPI_LINEAR = 0, EPI_ARGMAX = 1 };
@@ -101,7 +107,7 @@ struct WaveWalk {
     // every lane reads the first 16 bytes of the activations, a single cache line that every
     // compute unit already holds.
     __device__ __forceinline__ const u32x4 *addr(const Front &f) const {
-        const long long step = (long long)(t0 + f.tl) * p.S + (long long)f.c * p.SC + f.s_lo + f.si;
+        const long long step = (long long)(t0 + f.tl) * p.Srow + (long long)f.c * p.SC + f.s_lo + f.si;
         return real(f) ? p.w + step * 64 + lane : reinterpret_cast<const u32x4 *>(p.x);
     }
 };
@@ -113,9 +119,28 @@ struct WaveWalk {
 // accumulates rows 4g..4g+3 of token i (D).
 // LDS: [activation chunk][scales of the workgroup's tiles][2 x NW staging tiles][tile sums]
 // ------------------------------------------------------------------------------------
+//
+// When the activations of the whole K do not fit the LDS, re-staging them chunk by chunk makes
+// every workgroup read all of x from the L2 (256 x the bytes) with the weight stream stalled
+// meanwhile.  With a workspace the host instead splits K across workgroups (ksplit slices):
+// a workgroup stages only its slice of x, once, and writes fp32 partial tiles that
+// splitk_finalize_kernel sums in slice order.
 template <int MP, bool W16, int EPI, int NW, int D>
-__global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p) {
+__global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p0) {
     extern __shared__ __align__(16) unsigned char lds[];
+    GemmParams p = p0;
+    int G = gridDim.x, b = blockIdx.x, slice = 0;
+    if (p0.ksplit > 1) {
+        slice = b % p0.ksplit;
+        b = b / p0.ksplit;
+        G = G / p0.ksplit;
+        const int s0 = slice * p0.slice_steps;
+        p.S = min(p0.slice_steps, p0.S - s0);
+        p.SC = p.S;
+        p.C = 1;
+        p.w = p0.w + (long long)s0 * 64;
+        p.x = p0.x + (long long)s0 * (W16 ? kStepK16 : kStepK8);
+    }
     constexpr int NB = (MP == 32) ? 2 : 1;   // 16-token blocks
     constexpr int PPS = W16 ? 4 : 8;         // 16-byte activation pieces (8 k) per step
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
@@ -128,7 +153,7 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, mcol = lane & 15;
 
-    const int G = gridDim.x, b = blockIdx.x;
+    
     const int t0 = (int)(((long long)p.T * b) / G);
     const int t1 = (int)(((long long)p.T * (b + 1)) / G);
     const int ntiles = t1 - t0;
@@ -300,10 +325,15 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                                 const float v2 = rsum[nb].z * s4[2], v3 = rsum[nb].w * s4[3];
                                 if constexpr (EPI == EPI_LINEAR) {
                                     if (m < p.M) {
-                                        u32x2 o;
-                                        o.x = float_to_bf16_bits(v0) | (float_to_bf16_bits(v1) << 16);
-                                        o.y = float_to_bf16_bits(v2) | (float_to_bf16_bits(v3) << 16);
-                                        *reinterpret_cast<u32x2 *>(p.y + m * p.ldy + n0) = o;
+                                        if (p0.ksplit > 1) {
+                                            *reinterpret_cast<f32x4 *>(p0.part32 + ((long long)slice * p.M + m) * p.N + n0) =
+                                                rsum[nb];
+                                        } else {
+                                            u32x2 o;
+                                            o.x = float_to_bf16_bits(v0) | (float_to_bf16_bits(v1) << 16);
+                                            o.y = float_to_bf16_bits(v2) | (float_to_bf16_bits(v3) << 16);
+                                            *reinterpret_cast<u32x2 *>(p.y + m * p.ldy + n0) = o;
+                                        }
                                     }
                                 } else {
                                     // strictly greater keeps the lowest index inside a lane
@@ -501,6 +531,32 @@ __global__ __launch_bounds__(NW * 64) void stream_valu_kernel(const GemmParams p
 // Second stage of the fused verify: combine the per-workgroup keys, then count leading
 // draft matches.  One workgroup of 1024 threads, 32 threads per token position.
 // ------------------------------------------------------------------------------------
+// y[m, n] = bf16( (sum over K slices, in slice order, of part32[slice][m][n]) * delta_n ).
+// One thread per four consecutive outputs of a token.
+template <bool W16>
+__global__ __launch_bounds__(256) void splitk_finalize_kernel(const float *part32, int ksplit, int M, int N,
+                                                              const uint16_t *scales, uint16_t *y, long long ldy) {
+    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    const int nq = N / 4;
+    if (q >= (long long)M * nq) return;
+    const int m = (int)(q / nq), n0 = (int)(q % nq) * 4;
+    f32x4 acc = *reinterpret_cast<const f32x4 *>(part32 + (long long)m * N + n0);
+    for (int sl = 1; sl < ksplit; ++sl)
+        acc += *reinterpret_cast<const f32x4 *>(part32 + ((long long)sl * M + m) * N + n0);
+    float s4[4] = {1.f, 1.f, 1.f, 1.f};
+    if constexpr (!W16) {
+        const u32x2 sb = *reinterpret_cast<const u32x2 *>(scales + n0);
+        s4[0] = bf16_bits_to_float(sb.x & 0xFFFFu);
+        s4[1] = bf16_bits_to_float(sb.x >> 16);
+        s4[2] = bf16_bits_to_float(sb.y & 0xFFFFu);
+        s4[3] = bf16_bits_to_float(sb.y >> 16);
+    }
+    u32x2 o;
+    o.x = float_to_bf16_bits(acc.x * s4[0]) | (float_to_bf16_bits(acc.y * s4[1]) << 16);
+    o.y = float_to_bf16_bits(acc.z * s4[2]) | (float_to_bf16_bits(acc.w * s4[3]) << 16);
+    *reinterpret_cast<u32x2 *>(y + m * ldy + n0) = o;
+}
+
 __global__ __launch_bounds__(1024) void verify_finalize_kernel(const unsigned long long *partial, int nparts,
                                                                int MP, int M, int V, const int32_t *draft,
                                                                int n_draft, int32_t *out_argmax,

@@ -62,3 +62,29 @@ def test_qwen3_lmhead_verify_full_vocab(qb, j):
         torch.cuda.synchronize()
         assert np.array_equal(am.cpu().numpy(), t)
         assert int(acc.cpu()[0]) == jj == ref.accepted_length(base["argmax"], d)
+
+
+def test_qwen3_32b_layer_linears_all_outputs(qb):
+    """The larger model's layer shapes (hidden 5120, K up to 25600: activations chunked in LDS
+    from M = 8 on) at M in {8, 16, 32}, both forms of the linear."""
+    from oracle import quasar_w8a8_ref as a8
+    for li, (name, K, N) in enumerate(synth.QWEN3_32B_LAYER):
+        w = synth.normal_weights(N, K, seed=synth.seed_for(5, 0, li))
+        q_ref, s_ref = ref.quantize_weights(w)
+        wq, sc = qb.quantize_weights(f32_to_dev(w))
+        del w
+        assert np.array_equal(bf16_to_host(sc), s_ref), name
+        assert np.array_equal(qb.unpack_weights(wq, N, K).cpu().numpy(), q_ref), name
+        for M in (8, 16, 32):
+            xb = synth.activations_bf16(M, K, seed=synth.seed_for(5, 1, 10 * li + M))
+            xd = bf16_to_dev(xb)
+            y_ref = ref.w8_linear(xb, q_ref, s_ref)
+            for ws in (None, qb.make_workspace(M, N, K)):          # chunked, and K split across workgroups
+                y = qb.w8_linear(xd, wq, sc, N, workspace=ws)
+                torch.cuda.synchronize()
+                err = ref.rel_maxabs_err(ref.bf16_bits_to_f64(bf16_to_host(y)), y_ref)
+                print(name, "M", M, "workspace", ws is not None, "rel err", err, flush=True)
+                assert err <= TOL and err <= 4e-3
+            y8 = qb.w8a8_linear(xd, wq, sc, N)
+            torch.cuda.synchronize()
+            assert np.array_equal(bf16_to_host(y8), a8.w8a8_linear(xb, q_ref, s_ref)), (name, M)

@@ -176,6 +176,53 @@ def test_linear_repeatable_bits(qb):
         assert np.array_equal(run_linear(qb, xb, wq, sc, N, qb.PATH_MFMA), first)
 
 
+# K split across workgroups (taken when a workspace is passed and the activations of the whole
+# K do not fit the on-chip memory): same bars, plus agreement with the chunked path
+SHAPES_SPLITK = [
+    (8, 1024, 12288),     # 2 slices
+    (32, 512, 4096),      # 3 slices at M = 32
+    (12, 160, 25600),     # fewer tiles than tile groups
+    (32, 4096 + 16, 5120),
+    (16, 5120, 25600),    # the larger model's down projection
+    (32, 1024, 25600),    # 17+ slices
+]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES_SPLITK)
+def test_linear_split_k_with_workspace(qb, M, N, K):
+    say("linear split-K", M, N, K)
+    xb = synth.activations_bf16(M, K, seed=synth.seed_for(2, 2, M))
+    w = synth.normal_weights(N, K, seed=synth.seed_for(2, 3, M))
+    q_ref, s_ref, wq, sc = quantize_both(qb, w)
+    y_ref = ref.w8_linear(xb, q_ref, s_ref)
+    ws = qb.make_workspace(M, N, K)
+    assert ws.numel() >= 2 * M * N * 4                     # room for at least two slices of partial sums
+    x = bf16_to_dev(xb)
+    ws.fill_(0xFF)                                         # the workspace is scratch: garbage on entry
+    y = qb.w8_linear(x, wq, sc, N, workspace=ws)
+    torch.cuda.synchronize()
+    err = ref.rel_maxabs_err(ref.bf16_bits_to_f64(bf16_to_host(y)), y_ref)
+    y0 = qb.w8_linear(x, wq, sc, N)                        # chunked path
+    torch.cuda.synchronize()
+    err0 = ref.rel_maxabs_err(ref.bf16_bits_to_f64(bf16_to_host(y0)), y_ref)
+    say("   rel err split", err, "chunked", err0)
+    assert err <= TOL and err <= TOL_EXPECTED and err0 <= TOL_EXPECTED
+    y2 = qb.w8_linear(x, wq, sc, N, workspace=ws)          # repeatable bits
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+    # integer-valued inputs: every partial sum is exact, so the split must not change a bit
+    xi, wi_f, _, _ = synth.integer_case(M, N, K, seed=2000 + M, row_exponents=True)
+    qi, si, wqi, sci = quantize_both(qb, wi_f)
+    want = ref.f64_to_bf16_bits(ref.w8_linear(xi, qi, si))
+    got = bf16_to_host(qb.w8_linear(bf16_to_dev(xi), wqi, sci, N, workspace=ws))
+    assert np.array_equal(got, want)
+    # bf16-weight twin through the same split
+    wb = synth.to_bf16_bits(w)
+    wp = qb.pack_bf16_weights(f32_to_dev(w))
+    yb = qb.bf16_linear(x, wp, N, workspace=ws)
+    torch.cuda.synchronize()
+    assert ref.rel_maxabs_err(ref.bf16_bits_to_f64(bf16_to_host(yb)), ref.bf16_linear(xb, wb)) <= TOL_EXPECTED
+
+
 def test_bf16_twin_linear(qb):
     say("bf16 twin")
     for (M, N, K) in [(8, 1024, 1024), (5, 80, 448), (16, 256, 12288), (32, 128, 4096)]:
