@@ -316,6 +316,24 @@ def main() -> int:
             log(f"  vocabulary verify, single call, {label}: {us:7.2f} us  {head_bytes(1) / us / 1e3:7.1f} GB/s "
                 f"({head_bytes(1) / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
             detail["head_verify_" + ("w8a8" if label == "W8A8" else "w8") + "_us"] = us
+        # stochastic verification (T = 1): weight stream with fp32 logits, softmax statistics, decision
+        ua = torch.full((M - 1,), 0.5, dtype=torch.float32, device=dev)
+        us = torch.full((M,), 0.5, dtype=torch.float32, device=dev)
+        wss = torch.empty(qb.lib().quasar_sample_workspace_bytes(M, V), dtype=torch.uint8, device=dev)
+        fn = lambda: qb.lmhead_verify_sample(h0, head_q, head_s, V, draft, 1.0, ua, us, workspace=wss)
+        fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us_s = e0.elapsed_time(e1) * 1e3 / 10
+        log(f"  vocabulary verify with sampling (T = 1), single call: {us_s:7.2f} us  "
+            f"{head_bytes(1) / us_s / 1e3:7.1f} GB/s ({head_bytes(1) / us_s / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
+        detail["head_verify_sample_us"] = us_s
         calls88 = []
         for fn, a, nb, is_lin in calls8:
             if is_lin:

@@ -270,6 +270,36 @@ int quasar_sequence_prepare_w8a8(const quasar_linear_desc *linears, int64_t n_li
                                  void *workspace, size_t workspace_bytes, quasar_sequence *seq);
 
 /*
+ * ---- Stochastic verification, temperature T > 0 (Sec. 3.1: accept candidate i iff
+ * r < min(1, p/q), on rejection resample from norm(max(0, p - q)); Sec. 3.3 "Lossless
+ * Rejection Sampling": p is the softmax of the dequantised logits) ----
+ *
+ * The drafter is deterministic (prompt-lookup n-gram, as in the paper's experiments): q is a
+ * point mass on the proposed token, so candidate i is accepted iff u_accept[i] < p_i(x~_i), and
+ * the corrective token at the first rejected position n is drawn from p_n with the rejected
+ * token's mass removed.  If all n_draft candidates are accepted the bonus token is drawn from
+ * p at position n_draft, hence n_draft <= M - 1.  The draw is the inverse CDF in vocabulary
+ * order with u_sample[n]: token = min{ v : C(v) > u * C(V-1) }.
+ *   hidden, wq_packed, scales_bf16, V, draft_ids   as quasar_lmhead_verify
+ *   temperature     T > 0; p = softmax(logits / T), logits and softmax in fp32
+ *   u_accept        device [n_draft] fp32 in [0, 1): the r of the acceptance tests
+ *   u_sample        device [M] fp32 in [0, 1): entry n is used for the draw at position n
+ *   out_accept_len  device [1]: number of leading accepted candidates
+ *   out_next_token  device [1]: corrective or bonus token
+ *   out_p_draft     device [n_draft] fp32 or NULL: p_i(x~_i)
+ *   workspace       quasar_sample_workspace_bytes(M, V) bytes (the [M, V] fp32 logits live there)
+ * Three launches: the weight stream with fp32 outputs, softmax statistics per position, the
+ * decision.  int8 weights with bf16 activations only.
+ */
+size_t quasar_sample_workspace_bytes(int64_t M, int64_t V);
+int quasar_lmhead_verify_sample(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh,
+                                const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t V,
+                                const int32_t *draft_ids, int64_t n_draft, float temperature,
+                                const float *u_accept, const float *u_sample,
+                                int32_t *out_accept_len, int32_t *out_next_token, float *out_p_draft,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Measurement helpers (the bandwidth term of Eq. 11-12 measured directly).
  * quasar_read_stream reads `bytes` (multiple of 16) from `src` with the same
  * load pattern as the linear kernels and writes one checksum word per workgroup

@@ -29,6 +29,7 @@ EXPORTS = (
     "quasar_sequence_run",
     "quasar_quantize_weights_smoothed", "quasar_quantize_activations", "quasar_w8a8_linear",
     "quasar_w8a8_lmhead_verify", "quasar_sequence_prepare_w8a8",
+    "quasar_sample_workspace_bytes", "quasar_lmhead_verify_sample",
 )
 
 
@@ -91,6 +92,10 @@ def _load() -> ctypes.CDLL:
     lib.quasar_sequence_prepare.argtypes = [vp, i64, vp, i64, vp, sz, vp, sz, vp]
     lib.quasar_sequence_run.argtypes = [vp, vp, vp, sz, vp]
     lib.quasar_sequence_prepare_w8a8.argtypes = [vp, i64, vp, vp, vp, i64, vp, sz, vp, sz, vp]
+    lib.quasar_sample_workspace_bytes.argtypes = [i64, i64]
+    lib.quasar_sample_workspace_bytes.restype = sz
+    lib.quasar_lmhead_verify_sample.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, ctypes.c_float, vp, vp,
+                                                vp, vp, vp, vp, sz, vp]
     lib.quasar_quantize_weights_smoothed.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.quasar_quantize_activations.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
     lib.quasar_w8a8_linear.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, sz, vp]
@@ -256,6 +261,39 @@ def w8a8_lmhead_verify(hidden: torch.Tensor, wq_packed: torch.Tensor, scales: to
                                           _ptr(out_accept), _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream()))
     return out_argmax, out_accept
+
+
+def lmhead_verify_sample(hidden: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Tensor, V: int,
+                         draft_ids: torch.Tensor, temperature: float, u_accept: torch.Tensor,
+                         u_sample: torch.Tensor, workspace: torch.Tensor = None):
+    """Stochastic verification at temperature T > 0 against a deterministic drafter.
+    Returns (accept_len int32 [1], next_token int32 [1], p_draft fp32 [n_draft])."""
+    _dev(hidden, "hidden", torch.bfloat16)
+    _dev(wq_packed, "wq_packed", torch.int8)
+    _dev(scales, "scales", torch.bfloat16)
+    _dev(u_sample, "u_sample", torch.float32)
+    M, K = hidden.shape
+    n_draft = 0 if draft_ids is None else draft_ids.numel()
+    if n_draft:
+        _dev(draft_ids, "draft_ids", torch.int32)
+        _dev(u_accept, "u_accept", torch.float32)
+        if u_accept.numel() < n_draft:
+            raise ValueError("u_accept needs one entry per candidate")
+    if u_sample.numel() < M:
+        raise ValueError("u_sample needs one entry per position")
+    if workspace is None:
+        workspace = torch.empty(max(_lib.quasar_sample_workspace_bytes(M, V), 16), dtype=torch.uint8,
+                                device=hidden.device)
+    acc = torch.empty(1, dtype=torch.int32, device=hidden.device)
+    tok = torch.empty(1, dtype=torch.int32, device=hidden.device)
+    pd = torch.empty(max(n_draft, 1), dtype=torch.float32, device=hidden.device)
+    _check("quasar_lmhead_verify_sample",
+           _lib.quasar_lmhead_verify_sample(_ptr(hidden), M, K, hidden.stride(0), _ptr(wq_packed), _ptr(scales), V,
+                                            _ptr(draft_ids) if n_draft else None, n_draft, float(temperature),
+                                            _ptr(u_accept) if n_draft else None, _ptr(u_sample), _ptr(acc), _ptr(tok),
+                                            _ptr(pd), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream()))
+    return acc, tok, pd[:n_draft]
 
 
 def unpack_weights(wq_packed: torch.Tensor, N: int, K: int) -> torch.Tensor:

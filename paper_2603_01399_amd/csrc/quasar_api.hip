@@ -15,6 +15,7 @@
 #include "probe.hpp"
 #include "stream_gemm.hpp"
 #include "stream_sequence.hpp"
+#include "sample.hpp"
 #include "stream_w8a8.hpp"
 
 using namespace quasar;
@@ -494,6 +495,25 @@ bool plan_phase(SeqPhase &ph, int MP, bool w16, bool a8, int G, int &xs_bytes, i
     return true;
 }
 
+// The vocabulary projection with fp32 outputs (input of the stochastic verification): the
+// int8-weight streaming kernel in its default shape, logits to part32[m][n].
+int launch_logits(const GemmParams &base, int M, hipStream_t stream) {
+    GemmParams p = base;
+    p.Srow = p.S;
+    p.ksplit = 1;
+    const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
+    const int NB = MP == 32 ? 2 : 1;
+    const Plan pl = make_plan(p.T, p.S, 128 * MP, NB * 1024, 16, true);
+    if (pl.grid > kMaxGrid) return QUASAR_ERR_SHAPE;
+    p.SC = pl.SC;
+    p.C = pl.C;
+    p.xs_bytes = pl.xs_bytes;
+    p.sc_bytes = pl.sc_bytes;
+    if (MP == 8) return launch(stream_mfma_kernel<8, false, EPI_LOGITS, 16, 4>, pl.grid, 1024, pl.lds_bytes, stream, p);
+    if (MP == 16) return launch(stream_mfma_kernel<16, false, EPI_LOGITS, 16, 4>, pl.grid, 1024, pl.lds_bytes, stream, p);
+    return launch(stream_mfma_kernel<32, false, EPI_LOGITS, 16, 4>, pl.grid, 1024, pl.lds_bytes, stream, p);
+}
+
 template <int EPI>
 int launch_w8a8(const GemmParams &base, int M, hipStream_t stream, int *grid_out) {
     GemmParams p = base;
@@ -824,6 +844,48 @@ int quasar_w8a8_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int6
     const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
     hipLaunchKernelGGL(verify_finalize_kernel, dim3(1), dim3(1024), 0, st, p.partial, grid, MP, (int)M, (int)V,
                        draft_ids, (int)n_draft, out_argmax, out_accept_len);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+size_t quasar_sample_workspace_bytes(int64_t M, int64_t V) {
+    if (M < 1 || M > 32 || V < 16 || V % 16 || V > 0x7FFFFFF0ll) return 0;
+    // logits, per-(position, vocabulary block) softmax statistics
+    return (size_t)M * (size_t)V * sizeof(float) + 32u * (size_t)kSampleBlocks * 2u * sizeof(float);
+}
+
+int quasar_lmhead_verify_sample(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh, const int8_t *wq_packed,
+                                const uint16_t *scales_bf16, int64_t V, const int32_t *draft_ids, int64_t n_draft,
+                                float temperature, const float *u_accept, const float *u_sample,
+                                int32_t *out_accept_len, int32_t *out_next_token, float *out_p_draft,
+                                void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!hidden || !wq_packed || !scales_bf16 || !u_sample || !out_accept_len || !out_next_token)
+        return QUASAR_ERR_NULL;
+    if (n_draft > 0 && (!draft_ids || !u_accept)) return QUASAR_ERR_NULL;
+    if (const int e = check_mnk(M, V, K)) return e;
+    if (V > 0x7FFFFFF0ll) return QUASAR_ERR_SHAPE;
+    if (n_draft < 0 || n_draft > M - 1) return QUASAR_ERR_SHAPE;     // the bonus token needs one position more
+    if (!(temperature > 0.f) || !(temperature < 3.0e38f)) return QUASAR_ERR_SHAPE;
+    if (ldh < K || ldh % 8) return QUASAR_ERR_SHAPE;
+    if (!aligned(hidden, 16) || !aligned(wq_packed, 16) || !aligned(scales_bf16, 8) || !aligned(u_accept, 4) ||
+        !aligned(u_sample, 4) || !aligned(out_p_draft, 4))
+        return QUASAR_ERR_ALIGN;
+    if (!workspace || workspace_bytes < quasar_sample_workspace_bytes(M, V)) return QUASAR_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return QUASAR_ERR_ALIGN;
+    float *logits = static_cast<float *>(workspace);
+    float *stats = logits + (size_t)M * (size_t)V;
+    GemmParams p{};
+    p.x = hidden; p.ldx = ldh; p.w = reinterpret_cast<const u32x4 *>(wq_packed); p.scales = scales_bf16;
+    p.y = nullptr; p.ldy = 0; p.partial = nullptr; p.part32 = logits;
+    p.M = (int)M; p.N = (int)V; p.K = (int)K;
+    p.T = (int)(V / kTileRows);
+    p.S = (int)(K / kStepK8);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (const int e = launch_logits(p, (int)M, st)) return e;
+    const float inv_t = 1.0f / temperature;
+    hipLaunchKernelGGL(softmax_partial_kernel, dim3(kSampleBlocks, (unsigned int)M), dim3(256), 0, st, logits, (int)V,
+                       inv_t, stats);
+    hipLaunchKernelGGL(speculative_sample_kernel, dim3(1), dim3(1024), 0, st, logits, (int)V, (int)M, inv_t, draft_ids,
+                       (int)n_draft, u_accept, u_sample, stats, out_accept_len, out_next_token, out_p_draft);
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 

@@ -38,7 +38,9 @@ struct GemmParams {
     float *part32;
 };
 
-enum { EPI_LINEAR = 0, EPI_ARGMAX = 1 };
+// EPI_LOGITS: the linear epilogue with fp32 outputs, part32[m][n] (row stride N): the input of
+// the stochastic verification
+enum { EPI_LINEAR = 0, EPI_ARGMAX = 1, EPI_LOGITS = 2 };
 
 // ------------------------------------------------------------------------------------
 // Per-wave walk over the workgroup's (chunk, tile, step) sequence with a ring of D loads.
@@ -323,7 +325,11 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                                 const int m = mcol + 16 * nb;
                                 const float v0 = rsum[nb].x * s4[0], v1 = rsum[nb].y * s4[1];
                                 const float v2 = rsum[nb].z * s4[2], v3 = rsum[nb].w * s4[3];
-                                if constexpr (EPI == EPI_LINEAR) {
+                                if constexpr (EPI == EPI_LOGITS) {
+                                    if (m < p.M)
+                                        *reinterpret_cast<f32x4 *>(p0.part32 + (long long)m * p.N + n0) =
+                                            f32x4{v0, v1, v2, v3};
+                                } else if constexpr (EPI == EPI_LINEAR) {
                                     if (m < p.M) {
                                         if (p0.ksplit > 1) {
                                             *reinterpret_cast<f32x4 *>(p0.part32 + ((long long)slice * p.M + m) * p.N + n0) =

@@ -62,6 +62,34 @@ def test_qwen3_lmhead_verify_full_vocab(qb, j):
         torch.cuda.synchronize()
         assert np.array_equal(am.cpu().numpy(), t)
         assert int(acc.cpu()[0]) == jj == ref.accepted_length(base["argmax"], d)
+    # stochastic verification at the same size: the planted winners hold most of the mass at T = 1,
+    # the second candidate is replaced by an unlikely token and must be rejected
+    from oracle import quasar_sampling_ref as sp
+    from gpu_util import f32_to_dev as to_dev
+    print("oracle logits for the stochastic verification", flush=True)
+    logits = ref.w8_linear(h, q_ref, s_ref)
+    T = 1.0
+    p = sp.softmax(logits, T)
+    d = t[:M - 1].astype(np.int32).copy()
+    d[1] = int(np.argsort(p[1])[-5])
+    pd = p[np.arange(M - 1), d]
+    ua = (pd * 0.5).astype(np.float32)
+    ua[1] = np.float32(min(0.999, pd[1] + 0.5 * (1 - pd[1])))
+    us = np.full(M, 0.25, dtype=np.float32)
+    want = sp.speculative_verify(logits, d, T, ua.astype(np.float64), us.astype(np.float64))
+    acc, tok, pd_gpu = qb.lmhead_verify_sample(hd, wq, sc, V, i32_to_dev(d), T, to_dev(ua), to_dev(us))
+    torch.cuda.synchronize()
+    assert want["n_acc"] == 1 == int(acc.cpu()[0])
+    assert np.allclose(pd_gpu.cpu().numpy(), pd, rtol=1e-3)
+    tokv = int(tok.cpu()[0])
+    mass = p[1].copy()
+    mass[d[1]] = 0.0
+    c = np.cumsum(mass)
+    lo = c[tokv - 1] if tokv > 0 else 0.0
+    assert tokv != d[1] and mass[tokv] > 0
+    assert lo - 1e-4 * c[-1] <= float(us[1]) * c[-1] < c[tokv] + 1e-4 * c[-1]
+    if want["sample_margin"] > 1e-4:
+        assert tokv == want["token"]
 
 
 def test_qwen3_32b_layer_linears_all_outputs(qb):
