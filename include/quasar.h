@@ -300,6 +300,49 @@ int quasar_lmhead_verify_sample(const uint16_t *hidden, int64_t M, int64_t K, in
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * ---- 4-bit group-wise weights (Sec. 6 names lower-bit weights as the way to cut the
+ * verification traffic further; the quantiser is Eq. 6 at b = 4, the product Eq. 8 inside a
+ * group of input channels and Eq. 10 per group) ----
+ *
+ * One step size per output row and per group of 128 consecutive input channels:
+ *   delta[n, g] = bf16( fp32(max_{k in g} |W[n,k]|) / 7 ),
+ *   q[n, k]     = clamp( rint( fp32(W[n,k]) / delta[n, k/128] ), -7, 7 )   (fp32 division,
+ *                 round half to even; a group whose step size rounds to 0 gets all-zero codes),
+ *   y[m, n]     = bf16( sum_g delta[n, g] * sum_{k in g} x[m, k] * q[n, k] )   (fp32 sums).
+ * Codes and step sizes live in ONE packed buffer of quasar_w4_packed_bytes(N, K) bytes
+ * (N*K/2 bytes of codes + 2 bytes per row and group, interleaved so that a workgroup streams one
+ * contiguous range); K must be a multiple of 128, N of 16, other limits as quasar_w8_linear.
+ * Activations stay in bf16.  The accepted tolerance of the linear outputs is that of
+ * quasar_w8_linear; argmax and accepted length are exact outside logit ties.
+ */
+size_t quasar_w4_packed_bytes(int64_t N, int64_t K);   /* 0 on invalid shapes */
+
+/* Offline preparation: quantise w[N, K] (device, row stride ldw elements, QUASAR_F32 or
+ * QUASAR_BF16) into w4_packed (device, 16-byte aligned, quasar_w4_packed_bytes(N, K) bytes). */
+int quasar_quantize_weights_w4(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw,
+                               void *w4_packed, void *hip_stream);
+
+/* Inverse of the packing, for checking: codes to q_rowmajor (device int8 [N, K], 8-byte
+ * aligned), step sizes to scales_bf16 (device [N, K/128]). */
+int quasar_unpack_weights_w4(const void *w4_packed, int64_t N, int64_t K,
+                             int8_t *q_rowmajor, uint16_t *scales_bf16, void *hip_stream);
+
+/* y[M, N] (bf16, row stride ldy) from x[M, K] (bf16, row stride ldx) and packed 4-bit weights;
+ * arguments, alignment and errors as quasar_w8_linear (no workspace: K is never split across
+ * workgroups here). */
+int quasar_w4_linear(const uint16_t *x, int64_t M, int64_t K, int64_t ldx,
+                     const void *w4_packed, int64_t N,
+                     uint16_t *y, int64_t ldy, void *hip_stream);
+
+/* Vocabulary projection with 4-bit weights fused with the greedy acceptance decision (Eq. 2 at
+ * temperature 0); arguments and workspace as quasar_lmhead_verify. */
+int quasar_w4_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh,
+                            const void *w4_packed, int64_t V,
+                            const int32_t *draft_ids, int64_t n_draft,
+                            int32_t *out_argmax, int32_t *out_accept_len,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Measurement helpers (the bandwidth term of Eq. 11-12 measured directly).
  * quasar_read_stream reads `bytes` (multiple of 16) from `src` with the same
  * load pattern as the linear kernels and writes one checksum word per workgroup

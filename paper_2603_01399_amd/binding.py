@@ -30,6 +30,8 @@ EXPORTS = (
     "quasar_quantize_weights_smoothed", "quasar_quantize_activations", "quasar_w8a8_linear",
     "quasar_w8a8_lmhead_verify", "quasar_sequence_prepare_w8a8",
     "quasar_sample_workspace_bytes", "quasar_lmhead_verify_sample",
+    "quasar_w4_packed_bytes", "quasar_quantize_weights_w4", "quasar_unpack_weights_w4", "quasar_w4_linear",
+    "quasar_w4_lmhead_verify",
 )
 
 
@@ -96,6 +98,13 @@ def _load() -> ctypes.CDLL:
     lib.quasar_sample_workspace_bytes.restype = sz
     lib.quasar_lmhead_verify_sample.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, ctypes.c_float, vp, vp,
                                                 vp, vp, vp, vp, sz, vp]
+    lib.quasar_w4_packed_bytes.argtypes = [i64, i64]
+    lib.quasar_w4_packed_bytes.restype = sz
+    lib.quasar_set_tuning_w4.argtypes = [ci, ci]
+    lib.quasar_quantize_weights_w4.argtypes = [vp, ci, i64, i64, i64, vp, vp]
+    lib.quasar_unpack_weights_w4.argtypes = [vp, i64, i64, vp, vp, vp]
+    lib.quasar_w4_linear.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp]
+    lib.quasar_w4_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, sz, vp]
     lib.quasar_quantize_weights_smoothed.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.quasar_quantize_activations.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
     lib.quasar_w8a8_linear.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, sz, vp]
@@ -316,6 +325,74 @@ def w8_linear(x: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Tensor, N:
            _lib.quasar_w8_linear(_ptr(x), M, K, x.stride(0), _ptr(wq_packed), _ptr(scales), N,
                                  _ptr(y), y.stride(0), _ptr(workspace), ws_bytes, _stream()))
     return y
+
+
+def w4_packed_bytes(N: int, K: int) -> int:
+    return _lib.quasar_w4_packed_bytes(N, K)
+
+
+def set_tuning_w4(waves: int, depth: int) -> None:
+    _check("quasar_set_tuning_w4", _lib.quasar_set_tuning_w4(waves, depth))
+
+
+def quantize_weights_w4(w: torch.Tensor, w4_packed: torch.Tensor = None) -> torch.Tensor:
+    """w [N, K] fp32 or bf16 (last dim contiguous) -> packed 4-bit codes + group step sizes (uint8)."""
+    _dev(w, "w")
+    if w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be [N, K] with a contiguous last dimension")
+    dt = {torch.float32: F32, torch.bfloat16: BF16}.get(w.dtype)
+    if dt is None:
+        raise TypeError("w must be float32 or bfloat16")
+    N, K = w.shape
+    if w4_packed is None:
+        w4_packed = torch.empty(max(w4_packed_bytes(N, K), 1), dtype=torch.uint8, device=w.device)
+    _check("quasar_quantize_weights_w4",
+           _lib.quasar_quantize_weights_w4(_ptr(w), dt, N, K, w.stride(0), _ptr(w4_packed), _stream()))
+    return w4_packed
+
+
+def unpack_weights_w4(w4_packed: torch.Tensor, N: int, K: int):
+    """-> (codes int8 [N, K], step sizes bf16 [N, K // 128])."""
+    _dev(w4_packed, "w4_packed", torch.uint8)
+    q = torch.empty((N, K), dtype=torch.int8, device=w4_packed.device)
+    sc = torch.empty((N, max(K // 128, 1)), dtype=torch.bfloat16, device=w4_packed.device)
+    _check("quasar_unpack_weights_w4", _lib.quasar_unpack_weights_w4(_ptr(w4_packed), N, K, _ptr(q), _ptr(sc), _stream()))
+    return q, sc
+
+
+def w4_linear(x: torch.Tensor, w4_packed: torch.Tensor, N: int, y: torch.Tensor = None) -> torch.Tensor:
+    _dev(x, "x", torch.bfloat16)
+    _dev(w4_packed, "w4_packed", torch.uint8)
+    M, K = x.shape
+    if w4_packed.numel() < w4_packed_bytes(N, K):
+        raise ValueError("w4_packed is smaller than quasar_w4_packed_bytes(N, K)")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _check("quasar_w4_linear",
+           _lib.quasar_w4_linear(_ptr(x), M, K, x.stride(0), _ptr(w4_packed), N, _ptr(y), y.stride(0), _stream()))
+    return y
+
+
+def w4_lmhead_verify(hidden: torch.Tensor, w4_packed: torch.Tensor, V: int, draft_ids: torch.Tensor,
+                     workspace: torch.Tensor, out_argmax: torch.Tensor = None, out_accept: torch.Tensor = None):
+    _dev(hidden, "hidden", torch.bfloat16)
+    _dev(w4_packed, "w4_packed", torch.uint8)
+    M, K = hidden.shape
+    if w4_packed.numel() < w4_packed_bytes(V, K):
+        raise ValueError("w4_packed is smaller than quasar_w4_packed_bytes(V, K)")
+    n_draft = 0 if draft_ids is None else draft_ids.numel()
+    if n_draft:
+        _dev(draft_ids, "draft_ids", torch.int32)
+    if out_argmax is None:
+        out_argmax = torch.empty(M, dtype=torch.int32, device=hidden.device)
+    if out_accept is None:
+        out_accept = torch.empty(1, dtype=torch.int32, device=hidden.device)
+    _check("quasar_w4_lmhead_verify",
+           _lib.quasar_w4_lmhead_verify(_ptr(hidden), M, K, hidden.stride(0), _ptr(w4_packed), V,
+                                        _ptr(draft_ids) if n_draft else None, n_draft, _ptr(out_argmax),
+                                        _ptr(out_accept), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream()))
+    return out_argmax, out_accept
 
 
 def make_workspace(M: int, N: int, K: int, device="cuda") -> torch.Tensor:

@@ -124,4 +124,74 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const void *w, long long
     }
 }
 
+// ---- 4-bit group-wise weights -------------------------------------------------------------
+// Packed order: step s of tile t is 1056 contiguous bytes: 16 rows x 128 k of codes (lane
+// l = 16*g + i holds row i; dword j of the lane holds k = 32 j + 8 g + e, e = 0..7, as
+// code + 8 in nibble (e >> 1) + 4 (e & 1)), then the rows' 16 bf16 step sizes of this group.
+constexpr int kW4StepK = 128;
+constexpr int kW4StepBytes = 1056;
+
+// One workgroup (256 threads) per 16-row tile; 16 threads per row, each owns 8 consecutive k of
+// the current group, which is exactly one dword of the packed step.
+template <bool SRC_BF16>
+__global__ __launch_bounds__(256) void quantize_pack_w4_kernel(const void *w, long long ldw, int N, int K,
+                                                               unsigned char *packed) {
+    const int tid = threadIdx.x;
+    const int t = blockIdx.x;
+    const int S = K / kW4StepK;
+    const int r = tid >> 4, c = tid & 15;
+    const long long base = (long long)(t * kTileRows + r) * ldw;
+    for (int s = 0; s < S; ++s) {
+        float v[8];
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            v[e] = load_w<SRC_BF16>(w, base + (long long)s * kW4StepK + 8 * c + e);
+            amax = fmaxf(amax, fabsf(v[e]));
+        }
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+        unsigned int sb = float_to_bf16_bits(__fdiv_rn(amax, 7.0f));
+        float sc = bf16_bits_to_float(sb);
+        if (!(sc > 0.f)) { sb = 0; sc = 0.f; }
+        unsigned int word = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int code = 0;
+            if (sc > 0.f) {
+                float q = rintf(__fdiv_rn(v[e], sc));           // round half to even
+                q = fminf(fmaxf(q, -7.f), 7.f);
+                code = (int)q;
+            }
+            word |= (unsigned int)(code + 8) << (4 * ((e >> 1) + 4 * (e & 1)));
+        }
+        unsigned char *step = packed + ((long long)t * S + s) * kW4StepBytes;
+        const int j = c >> 2, g = c & 3;
+        reinterpret_cast<unsigned int *>(step)[(16 * g + r) * 4 + j] = word;
+        if (c == 0) reinterpret_cast<uint16_t *>(step + 1024)[r] = (uint16_t)sb;
+    }
+}
+
+// codes -> q[N, K] int8 row-major, step sizes -> scales[N, K / 128] bf16 (for checking)
+__global__ __launch_bounds__(256) void unpack_w4_kernel(const unsigned char *packed, int N, int K, int8_t *q,
+                                                        uint16_t *scales) {
+    const int S = K / kW4StepK;
+    const long long nwords = (long long)(N / kTileRows) * S * 256;
+    for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < nwords; idx += (long long)gridDim.x * 256) {
+        const int wd = (int)(idx & 255);
+        const long long ts = idx >> 8;
+        const int s = (int)(ts % S);
+        const long long t = ts / S;
+        const int l = wd >> 2, j = wd & 3;
+        const int g = l >> 4, i = l & 15;
+        const unsigned char *step = packed + ts * kW4StepBytes;
+        const unsigned int word = reinterpret_cast<const unsigned int *>(step)[wd];
+        int8_t *dst = q + (t * kTileRows + i) * (long long)K + (long long)s * kW4StepK + 32 * j + 8 * g;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[e] = (int8_t)((int)((word >> (4 * ((e >> 1) + 4 * (e & 1)))) & 15u) - 8);
+        if (wd < kTileRows)
+            scales[(t * kTileRows + wd) * (long long)S + s] = reinterpret_cast<const uint16_t *>(step + 1024)[wd];
+    }
+}
+
 }  // namespace quasar

@@ -17,6 +17,7 @@
 #include "stream_sequence.hpp"
 #include "sample.hpp"
 #include "stream_w8a8.hpp"
+#include "stream_w4.hpp"
 
 using namespace quasar;
 
@@ -535,6 +536,41 @@ int launch_w8a8(const GemmParams &base, int M, hipStream_t stream, int *grid_out
     return launch(stream_w8a8_kernel<32, EPI, 16, 8>, pl.grid, 1024, lds, stream, p);
 }
 
+std::atomic<int> g_w4_nw{16};
+std::atomic<int> g_w4_d{8};
+
+int check_mnk_w4(int64_t M, int64_t N, int64_t K) {
+    if (const int e = check_mnk(M, N, K)) return e;
+    return K % kStepK4 ? QUASAR_ERR_SHAPE : QUASAR_OK;
+}
+
+template <int EPI>
+int launch_w4(const GemmParams &base, int M, hipStream_t stream, int *grid_out) {
+    GemmParams p = base;
+    p.Srow = p.S;
+    p.ksplit = 1;
+    const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
+    const int NB = MP == 32 ? 2 : 1;
+    const int NW = g_w4_nw.load(), DD = g_w4_d.load();
+    // per step and token: 128 bf16 activations and one f32x4 group offset
+    const Plan pl = make_plan(p.T, p.S, 272 * MP, NB * 1024, NW, false);
+    if (pl.grid > kMaxGrid) return QUASAR_ERR_SHAPE;
+    p.SC = pl.SC;
+    p.C = pl.C;
+    p.xs_bytes = pl.xs_bytes;
+    p.sc_bytes = 0;
+    if (grid_out) *grid_out = pl.grid;
+#define QUASAR_LAUNCH_W4(MPV)                                                                              \
+    (NW == 16 ? (DD == 8 ? launch(stream_w4_kernel<MPV, EPI, 16, 8>, pl.grid, 1024, pl.lds_bytes, stream, p) \
+                         : launch(stream_w4_kernel<MPV, EPI, 16, 4>, pl.grid, 1024, pl.lds_bytes, stream, p)) \
+              : (DD == 16 ? launch(stream_w4_kernel<MPV, EPI, 8, 16>, pl.grid, 512, pl.lds_bytes, stream, p) \
+                          : launch(stream_w4_kernel<MPV, EPI, 8, 8>, pl.grid, 512, pl.lds_bytes, stream, p)))
+    if (MP == 8) return QUASAR_LAUNCH_W4(8);
+    if (MP == 16) return QUASAR_LAUNCH_W4(16);
+    return QUASAR_LAUNCH_W4(32);
+#undef QUASAR_LAUNCH_W4
+}
+
 template <int MP, bool W16, bool A8>
 int launch_sequence(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
     auto kernel = stream_sequence_kernel<MP, W16, A8, kSeqWaves, kSeqDepth>;
@@ -888,5 +924,95 @@ int quasar_lmhead_verify_sample(const uint16_t *hidden, int64_t M, int64_t K, in
                        (int)n_draft, u_accept, u_sample, stats, out_accept_len, out_next_token, out_p_draft);
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
+
+/* ---- 4-bit group-wise weights ---- */
+
+size_t quasar_w4_packed_bytes(int64_t N, int64_t K) {
+    if (check_mnk_w4(1, N, K)) return 0;
+    return (size_t)(N / kTileRows) * (size_t)(K / kStepK4) * (size_t)kStepBytes4;
+}
+
+/* development knob, not part of the documented contract: waves per workgroup and ring depth of
+ * the 4-bit kernels: (16, 8), (16, 4), (8, 16) or (8, 8) */
+int quasar_set_tuning_w4(int waves, int depth) {
+    if (!((waves == 16 && (depth == 8 || depth == 4)) || (waves == 8 && (depth == 16 || depth == 8))))
+        return QUASAR_ERR_DTYPE;
+    g_w4_nw = waves;
+    g_w4_d = depth;
+    return QUASAR_OK;
+}
+
+int quasar_quantize_weights_w4(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw, void *w4_packed,
+                               void *hip_stream) {
+    if (!w || !w4_packed) return QUASAR_ERR_NULL;
+    if (w_dtype != QUASAR_F32 && w_dtype != QUASAR_BF16) return QUASAR_ERR_DTYPE;
+    if (const int e = check_mnk_w4(1, N, K)) return e;
+    if (ldw < K) return QUASAR_ERR_SHAPE;
+    if (!aligned(w4_packed, 16) || !aligned(w, w_dtype == QUASAR_F32 ? 4 : 2)) return QUASAR_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int T = (int)(N / kTileRows);
+    if (w_dtype == QUASAR_F32)
+        hipLaunchKernelGGL(quantize_pack_w4_kernel<false>, dim3(T), dim3(256), 0, st, w, (long long)ldw, (int)N, (int)K,
+                           static_cast<unsigned char *>(w4_packed));
+    else
+        hipLaunchKernelGGL(quantize_pack_w4_kernel<true>, dim3(T), dim3(256), 0, st, w, (long long)ldw, (int)N, (int)K,
+                           static_cast<unsigned char *>(w4_packed));
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+int quasar_unpack_weights_w4(const void *w4_packed, int64_t N, int64_t K, int8_t *q_rowmajor, uint16_t *scales_bf16,
+                             void *hip_stream) {
+    if (!w4_packed || !q_rowmajor || !scales_bf16) return QUASAR_ERR_NULL;
+    if (const int e = check_mnk_w4(1, N, K)) return e;
+    if (!aligned(w4_packed, 16) || !aligned(q_rowmajor, 8) || !aligned(scales_bf16, 2)) return QUASAR_ERR_ALIGN;
+    const long long nwords = (long long)N * K / 8;
+    const int grid = (int)((nwords + 255) / 256 > 65535 ? 65535 : (nwords + 255) / 256);
+    hipLaunchKernelGGL(unpack_w4_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const unsigned char *>(w4_packed), (int)N, (int)K, q_rowmajor, scales_bf16);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+int quasar_w4_linear(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const void *w4_packed, int64_t N,
+                     uint16_t *y, int64_t ldy, void *hip_stream) {
+    if (!x || !w4_packed || !y) return QUASAR_ERR_NULL;
+    if (const int e = check_mnk_w4(M, N, K)) return e;
+    if (ldx < K || ldy < N || ldx % 8 || ldy % 8) return QUASAR_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(w4_packed, 16)) return QUASAR_ERR_ALIGN;
+    GemmParams p{};
+    p.x = x; p.ldx = ldx; p.w = static_cast<const u32x4 *>(w4_packed); p.scales = nullptr;
+    p.y = y; p.ldy = ldy; p.partial = nullptr;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.T = (int)(N / kTileRows);
+    p.S = (int)(K / kStepK4);
+    return launch_w4<EPI_LINEAR>(p, (int)M, static_cast<hipStream_t>(hip_stream), nullptr);
+}
+
+int quasar_w4_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh, const void *w4_packed,
+                            int64_t V, const int32_t *draft_ids, int64_t n_draft, int32_t *out_argmax,
+                            int32_t *out_accept_len, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!hidden || !w4_packed || !out_argmax || !out_accept_len) return QUASAR_ERR_NULL;
+    if (n_draft > 0 && !draft_ids) return QUASAR_ERR_NULL;
+    if (const int e = check_mnk_w4(M, V, K)) return e;
+    if (V > 0x7FFFFFF0ll) return QUASAR_ERR_SHAPE;
+    if (n_draft < 0 || n_draft > M) return QUASAR_ERR_SHAPE;
+    if (ldh < K || ldh % 8) return QUASAR_ERR_SHAPE;
+    if (!aligned(hidden, 16) || !aligned(w4_packed, 16)) return QUASAR_ERR_ALIGN;
+    if (!workspace || workspace_bytes < quasar_workspace_bytes(M, V, K)) return QUASAR_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return QUASAR_ERR_ALIGN;
+    GemmParams p{};
+    p.x = hidden; p.ldx = ldh; p.w = static_cast<const u32x4 *>(w4_packed); p.scales = nullptr;
+    p.y = nullptr; p.ldy = 0; p.partial = static_cast<unsigned long long *>(workspace);
+    p.M = (int)M; p.N = (int)V; p.K = (int)K;
+    p.T = (int)(V / kTileRows);
+    p.S = (int)(K / kStepK4);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int grid = 0;
+    if (const int e = launch_w4<EPI_ARGMAX>(p, (int)M, st, &grid)) return e;
+    const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
+    hipLaunchKernelGGL(verify_finalize_kernel, dim3(1), dim3(1024), 0, st, p.partial, grid, MP, (int)M, (int)V,
+                       draft_ids, (int)n_draft, out_argmax, out_accept_len);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
 
 }  // extern "C"
