@@ -40,6 +40,8 @@ def main() -> int:
                     "and the pure read stream (stderr)")
     ap.add_argument("--detail32", action="store_true", help="also time the Qwen3-32B layer shapes cold at "
                     "M = 8, 16, 32 (both forms of the linear)")
+    ap.add_argument("--detail4", action="store_true", help="also time the 4-bit group-wise weight form: every layer "
+                    "shape cold and the vocabulary verify, for each launch shape of the kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true", help="also run the plain copy kernel over 1 GiB (reference "
                     "for scaling hardware byte counters in rocprofv3 --pmc runs)")
@@ -189,15 +191,17 @@ def main() -> int:
         for _ in range(warmup):
             seq.run()
         torch.cuda.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        ev[0].record()
+        for i in range(steps):
             seq.run()
-        e1.record()
+            ev[i + 1].record()
         torch.cuda.synchronize()
         assert not seq.timed_out(), "a device-wide barrier timed out"
-        return e0.elapsed_time(e1) * 1e3 / steps
+        per = sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(steps))
+        if per[-1] > 1.5 * per[len(per) // 2]:
+            log(f"  note: uneven steps: min {per[0]:.1f} us, median {per[len(per) // 2]:.1f} us, max {per[-1]:.1f} us")
+        return ev[0].elapsed_time(ev[steps]) * 1e3 / steps
 
     # the timed step: ONE persistent launch (quasar_sequence_run) covering all linears + the head
     seq8 = make_sequence(calls8)
@@ -419,6 +423,70 @@ def main() -> int:
                         f"({nb / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
                     detail[f"q32b_{label}_{name}_M{Mv}_us"] = us
             del copies
+
+    if args.detail4:
+        # 4-bit group-wise weights (0.5 B per weight + 2 B per row and group of 128): the layer shapes cold
+        # (consecutive launches walk through >= 600 MB of distinct copies) and the vocabulary verify
+        w4_shapes = [("q/o_proj", 4096, 4096), ("k/v_proj", 4096, 1024), ("gate/up", 4096, 12288),
+                     ("down_proj", 12288, 4096)]
+        for name, K, N in w4_shapes:
+            nbw = qb.w4_packed_bytes(N, K)
+            ncopy = min(96, max(8, -(-600_000_000 // nbw)))
+            copies = []
+            for c in range(ncopy):
+                gen.manual_seed(synth.seed_for(6, c, len(copies)))
+                w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+                copies.append(qb.quantize_weights_w4(w))
+                del w
+            for Mv in (8, 16, 32):
+                x = torch.randn((Mv, K), device=dev).to(torch.bfloat16)
+                y = torch.empty((Mv, N), dtype=torch.bfloat16, device=dev)
+                for nw, dd in ((16, 4), (16, 2), (8, 8), (8, 4)):
+                    qb.set_tuning_w4(nw, dd)
+                    for wp in copies:
+                        qb.w4_linear(x, wp, N, y)
+                    torch.cuda.synchronize()
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(3):
+                        for wp in copies:
+                            qb.w4_linear(x, wp, N, y)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    us = e0.elapsed_time(e1) * 1e3 / (3 * ncopy)
+                    nb = nbw + 2 * Mv * K + 2 * Mv * N
+                    log(f"  W4 cold {name:10s} {K:6d}->{N:6d} M={Mv:2d} waves={nw:2d} depth={dd:2d}: {us:7.2f} us  "
+                        f"{nb / us / 1e3:7.1f} GB/s ({nb / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
+                    detail[f"w4_{name}_M{Mv}_w{nw}d{dd}_us"] = us
+            del copies
+        qb.set_tuning_w4(16, 2)
+        heads4 = []
+        for c in range(3):
+            gen.manual_seed(synth.seed_for(6, 200 + c, 0))
+            w = torch.randn((V, H), generator=gen, device=dev, dtype=torch.float32) * 0.02
+            heads4.append(qb.quantize_weights_w4(w))
+            del w
+        nbh = qb.w4_packed_bytes(V, H) + 2 * M * H + 4 * M + 4 * int(draft.numel()) + 4
+        for nw, dd in ((16, 4), (16, 2), (8, 8), (8, 4)):
+            qb.set_tuning_w4(nw, dd)
+            for wp in heads4:
+                qb.w4_lmhead_verify(h0, wp, V, draft, ws, out_argmax, out_accept)
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(4):
+                for wp in heads4:
+                    qb.w4_lmhead_verify(h0, wp, V, draft, ws, out_argmax, out_accept)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 12
+            log(f"  W4 vocabulary verify, single call, waves={nw:2d} depth={dd:2d}: {us:7.2f} us  {nbh / us / 1e3:7.1f} GB/s "
+                f"({nbh / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)")
+            detail[f"w4_head_verify_w{nw}d{dd}_us"] = us
+        qb.set_tuning_w4(16, 2)
+        del heads4
 
     # ------------------------------------------------------------- CPU oracle on the host cores
     cpu = None

@@ -537,11 +537,52 @@ int launch_w8a8(const GemmParams &base, int M, hipStream_t stream, int *grid_out
 }
 
 std::atomic<int> g_w4_nw{16};
-std::atomic<int> g_w4_d{8};
+std::atomic<int> g_w4_d{2};
 
 int check_mnk_w4(int64_t M, int64_t N, int64_t K) {
     if (const int e = check_mnk(M, N, K)) return e;
     return K % kStepK4 ? QUASAR_ERR_SHAPE : QUASAR_OK;
+}
+
+// LDS plan of the 4-bit kernel: activations of a K chunk (+ one f32x4 group offset per step and
+// token), staging for the pair-end sums, running pair sums when K is chunked.  When the running
+// sums of a workgroup's tiles leave too little room for activations the tiles are spread over more
+// workgroups than compute units.
+struct PlanW4 { int SC, C, xs_bytes, lds_bytes, grid; };
+bool plan_w4(int T, int S, int MP, int NW, PlanW4 &pl) {
+    const int NB = MP == 32 ? 2 : 1;
+    const int PAR = NB == 1 ? 2 : 1;
+    const int stage = PAR * NW * 2 * NB * 1024;
+    const int xps = 272 * MP;
+    int grid = device_cus();
+    if (grid > T) grid = T;
+    if ((long long)S * xps + stage + 64 <= kMaxLds) {
+        pl.SC = S;
+        pl.C = 1;
+        pl.xs_bytes = S * xps;
+        pl.lds_bytes = pl.xs_bytes + stage;
+    } else {
+        const int want = S < 8 ? S : 8;      // steps per chunk worth having
+        for (;;) {
+            const int tpw = (T + grid - 1) / grid;
+            const int sums = ((tpw + 1) / 2) * 2 * NB * 1024;
+            const int per = (kMaxLds - stage - sums - 64) / xps;
+            const bool can_grow = grid < T && grid * 2 <= kMaxGrid;
+            if (per >= want || (per >= 1 && !can_grow)) {
+                pl.C = (S + per - 1) / per;
+                pl.SC = (S + pl.C - 1) / pl.C;
+                pl.C = (S + pl.SC - 1) / pl.SC;
+                pl.xs_bytes = pl.SC * xps;
+                pl.lds_bytes = pl.xs_bytes + stage + sums;
+                break;
+            }
+            if (!can_grow) return false;
+            grid = grid * 2 > T ? T : grid * 2;
+        }
+    }
+    if (pl.lds_bytes < kMinLds) pl.lds_bytes = kMinLds;
+    pl.grid = grid;
+    return true;
 }
 
 template <int EPI>
@@ -550,21 +591,19 @@ int launch_w4(const GemmParams &base, int M, hipStream_t stream, int *grid_out) 
     p.Srow = p.S;
     p.ksplit = 1;
     const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
-    const int NB = MP == 32 ? 2 : 1;
     const int NW = g_w4_nw.load(), DD = g_w4_d.load();
-    // per step and token: 128 bf16 activations and one f32x4 group offset
-    const Plan pl = make_plan(p.T, p.S, 272 * MP, NB * 1024, NW, false);
-    if (pl.grid > kMaxGrid) return QUASAR_ERR_SHAPE;
+    PlanW4 pl{};
+    if (!plan_w4(p.T, p.S, MP, NW, pl) || pl.grid > kMaxGrid) return QUASAR_ERR_SHAPE;
     p.SC = pl.SC;
     p.C = pl.C;
     p.xs_bytes = pl.xs_bytes;
     p.sc_bytes = 0;
     if (grid_out) *grid_out = pl.grid;
 #define QUASAR_LAUNCH_W4(MPV)                                                                              \
-    (NW == 16 ? (DD == 8 ? launch(stream_w4_kernel<MPV, EPI, 16, 8>, pl.grid, 1024, pl.lds_bytes, stream, p) \
-                         : launch(stream_w4_kernel<MPV, EPI, 16, 4>, pl.grid, 1024, pl.lds_bytes, stream, p)) \
-              : (DD == 16 ? launch(stream_w4_kernel<MPV, EPI, 8, 16>, pl.grid, 512, pl.lds_bytes, stream, p) \
-                          : launch(stream_w4_kernel<MPV, EPI, 8, 8>, pl.grid, 512, pl.lds_bytes, stream, p)))
+    (NW == 16 ? (DD == 4 ? launch(stream_w4_kernel<MPV, EPI, 16, 4>, pl.grid, 1024, pl.lds_bytes, stream, p) \
+                         : launch(stream_w4_kernel<MPV, EPI, 16, 2>, pl.grid, 1024, pl.lds_bytes, stream, p)) \
+              : (DD == 8 ? launch(stream_w4_kernel<MPV, EPI, 8, 8>, pl.grid, 512, pl.lds_bytes, stream, p)   \
+                         : launch(stream_w4_kernel<MPV, EPI, 8, 4>, pl.grid, 512, pl.lds_bytes, stream, p)))
     if (MP == 8) return QUASAR_LAUNCH_W4(8);
     if (MP == 16) return QUASAR_LAUNCH_W4(16);
     return QUASAR_LAUNCH_W4(32);
@@ -932,10 +971,10 @@ size_t quasar_w4_packed_bytes(int64_t N, int64_t K) {
     return (size_t)(N / kTileRows) * (size_t)(K / kStepK4) * (size_t)kStepBytes4;
 }
 
-/* development knob, not part of the documented contract: waves per workgroup and ring depth of
- * the 4-bit kernels: (16, 8), (16, 4), (8, 16) or (8, 8) */
+/* development knob, not part of the documented contract: waves per workgroup and ring depth (in
+ * slots of two steps) of the 4-bit kernels: (16, 4), (16, 2), (8, 8) or (8, 4) */
 int quasar_set_tuning_w4(int waves, int depth) {
-    if (!((waves == 16 && (depth == 8 || depth == 4)) || (waves == 8 && (depth == 16 || depth == 8))))
+    if (!((waves == 16 && (depth == 4 || depth == 2)) || (waves == 8 && (depth == 8 || depth == 4))))
         return QUASAR_ERR_DTYPE;
     g_w4_nw = waves;
     g_w4_d = depth;

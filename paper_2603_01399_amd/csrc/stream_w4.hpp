@@ -11,10 +11,16 @@
 // matrix instruction: the accumulator of a group starts at -136 * (sum of the group's
 // activations), computed once per staged chunk in fp32.
 //
-// Per slot: 4 MFMA (16 rows x 32 k each) into a group accumulator, then four fused
+// A slot of the per-wave sequence is one k-step of a PAIR of neighbouring tiles of the
+// workgroup (the second of the pair is a dummy with step sizes 0 when the workgroup's tile
+// count is odd): two code loads and two step-size loads, 2 x 4 MFMA (16 rows x 32 k each)
+// into two group accumulators that read the same activations from LDS once, then fused
 // multiply-adds with the rows' step sizes into the running sums (Eq. 8 inside the group,
-// Eq. 10 per group).  Work split, ring discipline and the tile-end sum are those of the
-// 8-bit kernel.
+// Eq. 10 per group).  Per weight byte that halves the LDS reads, the scalar bookkeeping and
+// the tile-end barriers of a one-tile slot; with 4 bits per weight those, not the memory
+// system, are what limits the rate.  Addresses advance by constants (no multiplications per
+// slot).  Work split over the waves, ring discipline and the fixed-order tile-end sum are
+// those of the 8-bit kernel.
 #pragma once
 
 #include "stream_gemm.hpp"
@@ -27,12 +33,6 @@ constexpr unsigned int kW4Magic = 0x43004300u;   // bf16 128.0 twice
 constexpr float kW4Offset = 136.0f;  // 128 from the magic exponent + 8 from the stored code
 
 typedef const __attribute__((address_space(1))) u32x2 *global_u32x2_ptr;
-
-__device__ __forceinline__ u32x2 ring_refill2(const u32x2 *addr, const u32x2 &used) {
-    unsigned long long a = reinterpret_cast<unsigned long long>(addr);
-    asm volatile("" : "+v"(a) : "v"(used.x), "v"(used.y));
-    return __builtin_nontemporal_load(reinterpret_cast<global_u32x2_ptr>(a));
-}
 
 // one dword of eight 4-bit codes -> eight bf16 values 136 + code, in k order.  mask and magic
 // arrive in registers (see w4_constants): with literals the compiler needs an AND and an OR
@@ -54,13 +54,22 @@ __device__ __forceinline__ void w4_constants(unsigned int &mask, unsigned int &m
     asm volatile("" : "+v"(magic));
 }
 
+// 64-bit ring refill with a wave-uniform base address (scalar registers) and a per-lane byte
+// offset; the address is tied to the registers just consumed, as in ring_refill_at
+__device__ __forceinline__ u32x2 ring_refill2_at(unsigned long long base, unsigned int &lane_offset, const u32x2 &used) {
+    asm volatile("" : "+v"(lane_offset) : "v"(used.x), "v"(used.y));
+    return __builtin_nontemporal_load(reinterpret_cast<global_u32x2_ptr>(base + lane_offset));
+}
+
 // LDS: [activation chunk: [k/8][token] 16 B][group offsets: [step][token] f32x4]
-//      [2 x NW staging tiles][tile sums (C > 1)]
-// p.xs_bytes covers the first two; p.sc_bytes is 0.
+//      [PAR x NW x 2 staging tiles][pair sums (C > 1)]
+// p.xs_bytes covers the first two; p.sc_bytes is 0.  PAR = 2 staging areas used alternately
+// (one barrier per pair) when they fit, else one area and a second barrier.
 template <int MP, int EPI, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr int NB = (MP == 32) ? 2 : 1;
+    constexpr int PAR = (NB == 1) ? 2 : 1;
     constexpr int PPS = 16;                  // 16-byte activation pieces (8 k) per step
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
     constexpr int XB = 8;
@@ -75,11 +84,12 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
     const int t0 = (int)(((long long)p.T * b) / G);
     const int t1 = (int)(((long long)p.T * (b + 1)) / G);
     const int ntiles = t1 - t0;
+    const int npairs = (ntiles + 1) >> 1;
 
     u32x4 *xs = reinterpret_cast<u32x4 *>(lds);                                   // [SC*PPS][MP]
     f32x4 *gofs = reinterpret_cast<f32x4 *>(lds + p.SC * PPS * MP * 16);          // [SC][MP]
-    f32x4 *stage = reinterpret_cast<f32x4 *>(lds + p.xs_bytes);                   // [2][NW][NB][64]
-    f32x4 *accs = stage + 2 * NW * NB * 64;                                       // [ntiles][NB][64] (C > 1)
+    f32x4 *stage = reinterpret_cast<f32x4 *>(lds + p.xs_bytes);                   // [PAR][NW][2][NB][64]
+    f32x4 *accs = stage + PAR * NW * 2 * NB * 64;                                 // [npairs][2][NB][64] (C > 1)
 
     auto x_piece_load = [&](int c, int idx) -> u32x4 {
         const int scc = min(p.SC, p.S - c * p.SC);
@@ -109,56 +119,104 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
         }
     };
     // -136 * (sum of a group's activations) per (step of the chunk, token), four copies so that
-    // one LDS read fills the accumulator the group's first matrix instruction starts from
+    // one LDS read fills the accumulator the group's first matrix instruction starts from.
+    // Four neighbouring lanes share a (step, token): each sums four of its 16 pieces, two
+    // shuffles combine them (a fixed order).
     auto group_offsets = [&](int c) {
         const int scc = min(p.SC, p.S - c * p.SC);
-        for (int idx = tid; idx < scc * MP; idx += nthreads) {
+        const int total = ((scc * MP * 4 + nthreads - 1) / nthreads) * nthreads;   // whole waves take the shuffles
+        for (int idx4 = tid; idx4 < total; idx4 += nthreads) {
+            const int q = idx4 & 3, idx = idx4 >> 2;
             const int m = idx & (MP - 1), s = idx >> LMP;
             float sum = 0.f;
-#pragma unroll 4
-            for (int j = 0; j < PPS; ++j) {
-                const u32x4 v = xs[(s * PPS + j) * MP + m];
-                sum += __uint_as_float(v.x << 16);
-                sum += __uint_as_float(v.x & 0xFFFF0000u);
-                sum += __uint_as_float(v.y << 16);
-                sum += __uint_as_float(v.y & 0xFFFF0000u);
-                sum += __uint_as_float(v.z << 16);
-                sum += __uint_as_float(v.z & 0xFFFF0000u);
-                sum += __uint_as_float(v.w << 16);
-                sum += __uint_as_float(v.w & 0xFFFF0000u);
+            if (idx < scc * MP) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const u32x4 v = xs[(s * PPS + 4 * q + j) * MP + m];
+                    sum += __uint_as_float(v.x << 16);
+                    sum += __uint_as_float(v.x & 0xFFFF0000u);
+                    sum += __uint_as_float(v.y << 16);
+                    sum += __uint_as_float(v.y & 0xFFFF0000u);
+                    sum += __uint_as_float(v.z << 16);
+                    sum += __uint_as_float(v.z & 0xFFFF0000u);
+                    sum += __uint_as_float(v.w << 16);
+                    sum += __uint_as_float(v.w & 0xFFFF0000u);
+                }
             }
-            const float o = -kW4Offset * sum;
-            gofs[idx] = f32x4{o, o, o, o};
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            if (q == 0 && idx < scc * MP) {
+                const float o = -kW4Offset * sum;
+                gofs[idx] = f32x4{o, o, o, o};
+            }
         }
     };
 
-    WaveWalk<NW, D> walk{p, w, lane, t0, ntiles};
-    typename WaveWalk<NW, D>::Front ld;
-    walk.begin(ld);
-    // byte address of a slot's step (codes at + 16 lane, step sizes at + 1024 + 8 g); slots
-    // without a step read the first bytes of the activations, a line every compute unit holds
-    const unsigned char *wbytes = reinterpret_cast<const unsigned char *>(p.w);
-    auto slot_base = [&](const typename WaveWalk<NW, D>::Front &f, int &code_off, int &scale_off) {
-        const long long step = (long long)(t0 + f.tl) * p.Srow + (long long)f.c * p.SC + f.s_lo + f.si;
-        const bool real = walk.real(f);
-        code_off = real ? 16 * lane : 0;
-        scale_off = real ? 1024 + 8 * g : 0;
-        return real ? wbytes + step * kStepBytes4 : reinterpret_cast<const unsigned char *>(p.x);
+    // ---- load front: the (chunk, pair, step) position the next ring refill belongs to.  The
+    // address of tile A's step advances by constants; tile B's step lies one tile (Srow steps)
+    // further, or is tile A's again when the pair has no second tile.  Slots without a step
+    // (padding, waves without a share) read 16 (8) bytes of the workgroup's own first step, all
+    // lanes the same ones: one cache line per wave, in a region the workgroup reads anyway.
+    const unsigned long long wbase = reinterpret_cast<unsigned long long>(p.w);
+    const unsigned long long idle_addr = wbase + (unsigned long long)t0 * p.Srow * kStepBytes4 + 64u * w;
+    const unsigned int tile_bytes = (unsigned int)p.Srow * (unsigned int)kStepBytes4;
+    struct LoadFront {
+        int c, idx, si, pr, items, padded, nsl;
+        bool has;
+        unsigned long long addr;
+        unsigned int bofs;
     };
+    auto lf_slice = [&](LoadFront &f) {
+        const int scc = min(p.SC, p.S - f.c * p.SC);
+        const int s_lo = (scc * w) / NW;
+        const int spw = (scc * (w + 1)) / NW - s_lo;
+        f.nsl = max(spw, 1);
+        f.has = spw > 0;
+        f.items = npairs * f.nsl;
+        f.padded = ((f.items + D - 1) / D) * D;
+        f.idx = 0; f.si = 0; f.pr = 0;
+        f.addr = wbase + ((unsigned long long)t0 * p.Srow + (unsigned long long)f.c * p.SC + s_lo) * kStepBytes4;
+        f.bofs = ntiles > 1 ? tile_bytes : 0u;
+    };
+    auto lf_advance = [&](LoadFront &f) {
+        ++f.idx;
+        ++f.si;
+        f.addr += kStepBytes4;
+        if (f.si == f.nsl) {
+            f.si = 0;
+            ++f.pr;
+            f.addr += (unsigned long long)(2 * p.Srow - f.nsl) * kStepBytes4;
+            f.bofs = (2 * f.pr + 1 < ntiles) ? tile_bytes : 0u;
+        }
+        if (f.idx == f.padded) {
+            ++f.c;
+            if (f.c < p.C) lf_slice(f);
+            else { f.items = 0; f.padded = D; f.nsl = 1; f.has = false; f.idx = 0; f.si = 0; f.pr = 0; }
+        }
+    };
+    const unsigned int off_codes = 16u * lane, off_scales = 1024u + 8u * g;
+
+    LoadFront ld;
+    ld.c = 0;
+    lf_slice(ld);
 
     // requests in the order they are needed back: first activation batch, then the ring
     u32x4 xfirst[XB];
 #pragma unroll
     for (int i = 0; i < XB; ++i) xfirst[i] = x_piece_load(0, i * nthreads + tid);
-    u32x4 ring[D];
-    u32x2 sring[D];
+    u32x4 ringA[D], ringB[D];
+    u32x2 sclA[D], sclB[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-        int co, so;
-        const unsigned char *base = slot_base(ld, co, so);
-        ring[d] = ring_refill(reinterpret_cast<const u32x4 *>(base + co), u32x4{0u, 0u, 0u, 0u});
-        sring[d] = ring_refill2(reinterpret_cast<const u32x2 *>(base + so), u32x2{0u, 0u});
-        walk.advance(ld);
+        const bool real = ld.has && ld.idx < ld.items;
+        const unsigned long long a = real ? ld.addr : idle_addr;
+        const unsigned long long bb = a + (real ? ld.bofs : 0u);
+        unsigned int oc = real ? off_codes : 0u, os = real ? off_scales : 0u;
+        ringA[d] = ring_refill_at(a, oc, u32x4{0u, 0u, 0u, 0u});
+        ringB[d] = ring_refill_at(bb, oc, u32x4{0u, 0u, 0u, 0u});
+        sclA[d] = ring_refill2_at(a, os, u32x2{0u, 0u});
+        sclB[d] = ring_refill2_at(bb, os, u32x2{0u, 0u});
+        lf_advance(ld);
     }
     {
         const int npieces = min(p.SC, p.S) * PPS * MP;
@@ -173,9 +231,9 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
         lds_barrier();
     }
 
-    f32x4 acc[NB];
+    f32x4 accA[NB], accB[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < NB; ++nb) accA[nb] = accB[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
     float bestv[NB];
     unsigned int besti[NB];
 #pragma unroll
@@ -187,7 +245,7 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
 
     for (int c = 0; c < p.C; ++c) {
         if (c > 0) {
-            // every wave has passed the previous chunk's last tile barrier: the chunk's
+            // every wave has passed the previous chunk's last pair barrier: the chunk's
             // activations are no longer read
             x_stage(c, 0);
             // full drain: the staging loads are conditional, and without a known-empty load
@@ -197,103 +255,130 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
             group_offsets(c);
             lds_barrier();
         }
-        typename WaveWalk<NW, D>::Front cs;
-        walk.slice(c, cs);
-        int tl = 0, si = 0;
-        const int rounds = cs.padded / D;
+        const int scc = min(p.SC, p.S - c * p.SC);
+        const int s_lo = (scc * w) / NW;
+        const int spw = (scc * (w + 1)) / NW - s_lo;
+        const int nsl = max(spw, 1);
+        const bool has = spw > 0;
+        const int items = npairs * nsl;
+        const int rounds = (items + D - 1) / D;
+        int pr = 0, si = 0;
         for (int r = 0; r < rounds; ++r) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 const int idx = r * D + d;
-                const bool in_range = idx < cs.items;
-                const bool valid = in_range && si < cs.spw;
-                const u32x4 wv = ring[d];
-                u32x2 sv = sring[d];
-                if (!valid) sv = u32x2{0u, 0u};      // step sizes 0: the slot contributes nothing
-                const int step_in_chunk = valid ? cs.s_lo + si : 0;
-                const int piece0 = step_in_chunk * PPS;
-                f32x4 accg[NB];
+                const bool in_range = idx < items;
+                const bool valid = in_range && has;
+                const bool validB = valid && (2 * pr + 1 < ntiles);
+                const u32x4 wA = ringA[d], wB = ringB[d];
+                u32x2 svA = sclA[d], svB = sclB[d];
+                if (!validB) svB = u32x2{0u, 0u};      // no second tile: step sizes 0, it contributes nothing
+                if (valid) {
+                    // slots without a step skip the arithmetic (a wave-uniform branch); their loads
+                    // below are still issued, one per ring entry and slot
+                    const int step_in_chunk = s_lo + si;
+                    const int piece0 = step_in_chunk * PPS;
+                    f32x4 gA[NB], gB[NB];
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) accg[nb] = gofs[step_in_chunk * MP + xm + 16 * nb];
-                const unsigned int wd[4] = {wv.x, wv.y, wv.z, wv.w};
+                    for (int nb = 0; nb < NB; ++nb) gA[nb] = gB[nb] = gofs[step_in_chunk * MP + xm + 16 * nb];
+                    const unsigned int wdA[4] = {wA.x, wA.y, wA.z, wA.w};
+                    const unsigned int wdB[4] = {wB.x, wB.y, wB.z, wB.w};
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const bf16x8 a = w4_to_bf16x8(wd[j], nib_mask, nib_magic);
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const u32x4 bx = xs[(piece0 + 4 * j + g) * MP + xm + 16 * nb];
-                        accg[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bx),
-                                                                           accg[nb], 0, 0, 0);
-                    }
-                }
-                {
-                    int co, so;
-                    const unsigned char *base = slot_base(ld, co, so);
-                    ring[d] = ring_refill(reinterpret_cast<const u32x4 *>(base + co), wv);
-                    sring[d] = ring_refill2(reinterpret_cast<const u32x2 *>(base + so), sv);
-                    walk.advance(ld);
-                }
-                {
-                    const float s0 = __uint_as_float(sv.x << 16), s1 = __uint_as_float(sv.x & 0xFFFF0000u);
-                    const float s2 = __uint_as_float(sv.y << 16), s3 = __uint_as_float(sv.y & 0xFFFF0000u);
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        acc[nb].x = __builtin_fmaf(s0, accg[nb].x, acc[nb].x);
-                        acc[nb].y = __builtin_fmaf(s1, accg[nb].y, acc[nb].y);
-                        acc[nb].z = __builtin_fmaf(s2, accg[nb].z, acc[nb].z);
-                        acc[nb].w = __builtin_fmaf(s3, accg[nb].w, acc[nb].w);
-                    }
-                }
-                if (in_range && si == cs.nsl - 1) {
-                    // ---- tile end: cross-wave sum through LDS, fixed order
-                    f32x4 *st = stage + (parity * NW) * NB * 64;
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        st[(w * NB + nb) * 64 + lane] = acc[nb];
-                        acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    }
-                    lds_barrier();
-                    if (w == (tl % NW)) {
-                        f32x4 rsum[NB];
+                    for (int j = 0; j < 4; ++j) {
+                        const bf16x8 aA = w4_to_bf16x8(wdA[j], nib_mask, nib_magic);
+                        const bf16x8 aB = w4_to_bf16x8(wdB[j], nib_mask, nib_magic);
 #pragma unroll
                         for (int nb = 0; nb < NB; ++nb) {
-                            rsum[nb] = st[nb * 64 + lane];
-#pragma unroll
-                            for (int ww = 1; ww < NW; ++ww) rsum[nb] += st[(ww * NB + nb) * 64 + lane];
-                            if (p.C > 1) {
-                                f32x4 *a = accs + (tl * NB + nb) * 64 + lane;
-                                if (c > 0) rsum[nb] += *a;
-                                if (c < p.C - 1) *a = rsum[nb];
-                            }
+                            const bf16x8 bx = __builtin_bit_cast(bf16x8, xs[(piece0 + 4 * j + g) * MP + xm + 16 * nb]);
+                            gA[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aA, bx, gA[nb], 0, 0, 0);
+                            gB[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aB, bx, gB[nb], 0, 0, 0);
                         }
-                        if (c == p.C - 1) {
-                            const int n0 = (t0 + tl) * kTileRows + 4 * g;
+                    }
+                    const float a0 = __uint_as_float(svA.x << 16), a1 = __uint_as_float(svA.x & 0xFFFF0000u);
+                    const float a2 = __uint_as_float(svA.y << 16), a3 = __uint_as_float(svA.y & 0xFFFF0000u);
+                    const float b0 = __uint_as_float(svB.x << 16), b1 = __uint_as_float(svB.x & 0xFFFF0000u);
+                    const float b2 = __uint_as_float(svB.y << 16), b3 = __uint_as_float(svB.y & 0xFFFF0000u);
 #pragma unroll
-                            for (int nb = 0; nb < NB; ++nb) {
-                                const int m = mcol + 16 * nb;
-                                const float v0 = rsum[nb].x, v1 = rsum[nb].y, v2 = rsum[nb].z, v3 = rsum[nb].w;
-                                if constexpr (EPI == EPI_LINEAR) {
-                                    if (m < p.M) {
-                                        u32x2 o;
-                                        o.x = float_to_bf16_bits(v0) | (float_to_bf16_bits(v1) << 16);
-                                        o.y = float_to_bf16_bits(v2) | (float_to_bf16_bits(v3) << 16);
-                                        *reinterpret_cast<u32x2 *>(p.y + m * p.ldy + n0) = o;
+                    for (int nb = 0; nb < NB; ++nb) {
+                        accA[nb].x = __builtin_fmaf(a0, gA[nb].x, accA[nb].x);
+                        accA[nb].y = __builtin_fmaf(a1, gA[nb].y, accA[nb].y);
+                        accA[nb].z = __builtin_fmaf(a2, gA[nb].z, accA[nb].z);
+                        accA[nb].w = __builtin_fmaf(a3, gA[nb].w, accA[nb].w);
+                        accB[nb].x = __builtin_fmaf(b0, gB[nb].x, accB[nb].x);
+                        accB[nb].y = __builtin_fmaf(b1, gB[nb].y, accB[nb].y);
+                        accB[nb].z = __builtin_fmaf(b2, gB[nb].z, accB[nb].z);
+                        accB[nb].w = __builtin_fmaf(b3, gB[nb].w, accB[nb].w);
+                    }
+                }
+                {
+                    const bool real = ld.has && ld.idx < ld.items;
+                    const unsigned long long a = real ? ld.addr : idle_addr;
+                    const unsigned long long bb = a + (real ? ld.bofs : 0u);
+                    unsigned int oc = real ? off_codes : 0u, os = real ? off_scales : 0u;
+                    ringA[d] = ring_refill_at(a, oc, wA);
+                    ringB[d] = ring_refill_at(bb, oc, wB);
+                    sclA[d] = ring_refill2_at(a, os, svA);
+                    sclB[d] = ring_refill2_at(bb, os, svB);
+                    lf_advance(ld);
+                }
+                if (in_range && si == nsl - 1) {
+                    // ---- pair end: cross-wave sum through LDS, fixed order
+                    if constexpr (PAR == 1) lds_barrier();   // the previous pair's sums have been read
+                    f32x4 *st = stage + (parity * NW) * 2 * NB * 64;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        st[((w * 2 + 0) * NB + nb) * 64 + lane] = accA[nb];
+                        st[((w * 2 + 1) * NB + nb) * 64 + lane] = accB[nb];
+                        accA[nb] = accB[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                    lds_barrier();
+                    if (w == (pr % NW)) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            const int tl = 2 * pr + h;
+                            if (tl < ntiles) {
+                                f32x4 rsum[NB];
+#pragma unroll
+                                for (int nb = 0; nb < NB; ++nb) {
+                                    rsum[nb] = st[(h * NB + nb) * 64 + lane];
+#pragma unroll
+                                    for (int ww = 1; ww < NW; ++ww) rsum[nb] += st[((ww * 2 + h) * NB + nb) * 64 + lane];
+                                    if (p.C > 1) {
+                                        f32x4 *a = accs + ((pr * 2 + h) * NB + nb) * 64 + lane;
+                                        if (c > 0) rsum[nb] += *a;
+                                        if (c < p.C - 1) *a = rsum[nb];
                                     }
-                                } else {
-                                    // strictly greater keeps the lowest index inside a lane
-                                    if (v0 > bestv[nb]) { bestv[nb] = v0; besti[nb] = n0; }
-                                    if (v1 > bestv[nb]) { bestv[nb] = v1; besti[nb] = n0 + 1; }
-                                    if (v2 > bestv[nb]) { bestv[nb] = v2; besti[nb] = n0 + 2; }
-                                    if (v3 > bestv[nb]) { bestv[nb] = v3; besti[nb] = n0 + 3; }
+                                }
+                                if (c == p.C - 1) {
+                                    const int n0 = (t0 + tl) * kTileRows + 4 * g;
+#pragma unroll
+                                    for (int nb = 0; nb < NB; ++nb) {
+                                        const int m = mcol + 16 * nb;
+                                        const float v0 = rsum[nb].x, v1 = rsum[nb].y, v2 = rsum[nb].z, v3 = rsum[nb].w;
+                                        if constexpr (EPI == EPI_LINEAR) {
+                                            if (m < p.M) {
+                                                u32x2 o;
+                                                o.x = float_to_bf16_bits(v0) | (float_to_bf16_bits(v1) << 16);
+                                                o.y = float_to_bf16_bits(v2) | (float_to_bf16_bits(v3) << 16);
+                                                *reinterpret_cast<u32x2 *>(p.y + m * p.ldy + n0) = o;
+                                            }
+                                        } else {
+                                            // strictly greater keeps the lowest index inside a lane
+                                            if (v0 > bestv[nb]) { bestv[nb] = v0; besti[nb] = n0; }
+                                            if (v1 > bestv[nb]) { bestv[nb] = v1; besti[nb] = n0 + 1; }
+                                            if (v2 > bestv[nb]) { bestv[nb] = v2; besti[nb] = n0 + 2; }
+                                            if (v3 > bestv[nb]) { bestv[nb] = v3; besti[nb] = n0 + 3; }
+                                        }
+                                    }
                                 }
                             }
                         }
                     }
-                    parity ^= 1;
+                    if constexpr (PAR == 2) parity ^= 1;
                 }
                 if (in_range) {
                     ++si;
-                    if (si >= cs.nsl) { si = 0; ++tl; }
+                    if (si >= nsl) { si = 0; ++pr; }
                 }
             }
         }
@@ -302,7 +387,7 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
     if constexpr (EPI == EPI_ARGMAX) {
         // per wave: combine the four k-groups' row subsets, then combine waves, then publish
         unsigned long long *red = reinterpret_cast<unsigned long long *>(stage);   // [NW][MP]
-        lds_barrier();   // all tile-end reads of the staging area are done
+        lds_barrier();   // all pair-end reads of the staging area are done
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             unsigned long long key = argmax_key(bestv[nb], besti[nb]);

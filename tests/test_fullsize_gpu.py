@@ -116,3 +116,48 @@ def test_qwen3_32b_layer_linears_all_outputs(qb):
             y8 = qb.w8a8_linear(xd, wq, sc, N)
             torch.cuda.synchronize()
             assert np.array_equal(bf16_to_host(y8), a8.w8a8_linear(xb, q_ref, s_ref)), (name, M)
+
+
+def test_w4_qwen3_8b_layer_and_full_vocab(qb):
+    """The 4-bit group-wise form at the same sizes: every linear of the layer at M in {1, 8, 16}
+    (codes and step sizes bit-exact, all outputs within tolerance) and the vocabulary verify at
+    V = 151936 (argmax and accepted length exact on planted winners)."""
+    from oracle import quasar_w4_ref as w4
+    for li, (name, K, N) in enumerate(synth.QWEN3_8B_LAYER):
+        if name in ("v_proj", "up_proj"):               # same shapes as k_proj / gate_proj
+            continue
+        w = synth.normal_weights(N, K, seed=synth.seed_for(9, 0, li))
+        q_ref, s_ref = w4.quantize_weights_w4(w)
+        wp = qb.quantize_weights_w4(f32_to_dev(w))
+        q_gpu, s_gpu = qb.unpack_weights_w4(wp, N, K)
+        assert np.array_equal(q_gpu.cpu().numpy(), q_ref), name
+        assert np.array_equal(bf16_to_host(s_gpu), s_ref), name
+        for M in (1, 8, 16):
+            xb = synth.activations_bf16(M, K, seed=synth.seed_for(9, 1, 10 * li + M))
+            y = qb.w4_linear(bf16_to_dev(xb), wp, N)
+            torch.cuda.synchronize()
+            err = ref.rel_maxabs_err(ref.bf16_bits_to_f64(bf16_to_host(y)), w4.w4_linear(xb, q_ref, s_ref))
+            print("w4", name, "M", M, "rel err", err, flush=True)
+            assert err <= TOL and err <= 4e-3
+    M, K, V = 8, synth.QWEN3_8B_HIDDEN, synth.QWEN3_VOCAB
+    h = synth.activations_bf16(M, K, seed=synth.seed_for(9, 2, 0))
+    w = synth.normal_weights(V, K, seed=synth.seed_for(9, 2, 1))
+    t = synth.distinct_targets(M, V, seed=synth.seed_for(9, 2, 2))
+    synth.plant_targets(w, h, t)
+    print("w4 vocabulary: quantising on both sides", flush=True)
+    q_ref, s_ref = w4.quantize_weights_w4(w)
+    wp = qb.quantize_weights_w4(f32_to_dev(w))
+    del w
+    q_gpu, s_gpu = qb.unpack_weights_w4(wp, V, K)
+    assert np.array_equal(bf16_to_host(s_gpu), s_ref)
+    assert np.array_equal(q_gpu.cpu().numpy(), q_ref)
+    del q_gpu, s_gpu
+    print("w4 vocabulary: oracle logits", flush=True)
+    base = w4.w4_lmhead_verify(h, q_ref, s_ref, np.zeros(0, np.int32))
+    assert np.array_equal(base["argmax"], t)
+    assert np.all(base["top1"] - base["top2"] > TOL * base["maxabs"])
+    ws = qb.make_workspace(M, V, K)
+    for jj in (0, 3, 7):
+        d = synth.draft_with_matches(t, jj, V, M - 1)
+        am, acc = qb.w4_lmhead_verify(bf16_to_dev(h), wp, V, i32_to_dev(d), ws)
+        assert np.array_equal(am.cpu().numpy(), t) and int(acc.cpu()[0]) == jj
