@@ -424,6 +424,28 @@ def main() -> int:
                     detail[f"q32b_{label}_{name}_M{Mv}_us"] = us
             del copies
 
+    # the drafter's share of a step (T_draft of the throughput model): host time of one proposal and
+    # of one appended token on a synthetic repetitive context
+    rng_d = np.random.Generator(np.random.Philox(synth.seed_for(7, 0, 0)))
+    phrases = [rng_d.integers(0, V, size=24) for _ in range(8)]
+    ctx = np.concatenate([phrases[int(i)] for i in rng_d.integers(0, 8, size=342)]).astype(np.int32)[:8192]
+    drafter = qb.Drafter(1, 4, capacity_hint=16384)
+    t0 = time.perf_counter()
+    drafter.append(ctx)
+    t_app = (time.perf_counter() - t0) / ctx.size
+    lib, hnd = qb.lib(), drafter._h
+    import ctypes
+    buf, nd, kk = (ctypes.c_int32 * 8)(), ctypes.c_int64(0), ctypes.c_int(0)
+    t0 = time.perf_counter()
+    for _ in range(2000):
+        lib.quasar_drafter_propose(hnd, M - 1, buf, ctypes.byref(nd), ctypes.byref(kk))
+    t_prop = (time.perf_counter() - t0) / 2000
+    log(f"n-gram drafter (host): {t_prop * 1e6:.2f} us per proposal incl. the ctypes call, {t_app * 1e9:.0f} ns per appended "
+        f"token, context {ctx.size} tokens, lookup 1..4, gamma {M - 1} (proposed {nd.value} tokens at lookup length {kk.value})")
+    detail["drafter_us_per_proposal"] = t_prop * 1e6
+    detail["drafter_ns_per_appended_token"] = t_app * 1e9
+    drafter.close()
+
     if args.detail4:
         # 4-bit group-wise weights (0.5 B per weight + 2 B per row and group of 128): the layer shapes cold
         # (consecutive launches walk through >= 600 MB of distinct copies) and the vocabulary verify

@@ -343,6 +343,31 @@ int quasar_w4_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * ---- Prompt-lookup n-gram drafter (Sec. 2: drafts by n-gram matching against the context;
+ * Sec. 4 "Implementation Details": lookup length adjusted dynamically between a minimum and a
+ * maximum, 1 and 4 in the paper; Sec. 4.4: range (K_min, K_max), gamma speculative tokens) ----
+ *
+ * HOST code and HOST pointers throughout; no GPU work, no stream.  The context (prompt plus
+ * accepted tokens) only grows.  A proposal tries the lookup lengths from k_max down to k_min;
+ * for a length k the pattern is the last k tokens, a match is an earlier start s < n - k with the
+ * same k tokens (it may overlap the pattern), the most recent match of the first length that
+ * has one is taken, and the draft is the up to gamma tokens that followed it (cut at the end of
+ * the context).  No match: n_draft = 0.  An object is not safe for concurrent calls.
+ *   quasar_drafter_create   NULL on invalid arguments (1 <= k_min <= k_max <= 64) or out of memory;
+ *                           capacity_hint = expected context length (0 if unknown)
+ *   quasar_drafter_append   extends the context by n tokens (copied)
+ *   quasar_drafter_propose  out_draft: host [gamma]; *out_n_draft tokens written;
+ *                           *out_lookup_len (may be NULL) = the length that matched, 0 if none
+ */
+typedef struct quasar_drafter quasar_drafter;
+quasar_drafter *quasar_drafter_create(int k_min, int k_max, int64_t capacity_hint);
+void quasar_drafter_destroy(quasar_drafter *drafter);
+int quasar_drafter_append(quasar_drafter *drafter, const int32_t *tokens, int64_t n);
+int64_t quasar_drafter_length(const quasar_drafter *drafter);   /* -1 for NULL */
+int quasar_drafter_propose(const quasar_drafter *drafter, int64_t gamma, int32_t *out_draft,
+                           int64_t *out_n_draft, int *out_lookup_len);
+
+/*
  * Measurement helpers (the bandwidth term of Eq. 11-12 measured directly).
  * quasar_read_stream reads `bytes` (multiple of 16) from `src` with the same
  * load pattern as the linear kernels and writes one checksum word per workgroup

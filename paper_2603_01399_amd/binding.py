@@ -32,6 +32,8 @@ EXPORTS = (
     "quasar_sample_workspace_bytes", "quasar_lmhead_verify_sample",
     "quasar_w4_packed_bytes", "quasar_quantize_weights_w4", "quasar_unpack_weights_w4", "quasar_w4_linear",
     "quasar_w4_lmhead_verify",
+    "quasar_drafter_create", "quasar_drafter_destroy", "quasar_drafter_append", "quasar_drafter_length",
+    "quasar_drafter_propose",
 )
 
 
@@ -105,6 +107,14 @@ def _load() -> ctypes.CDLL:
     lib.quasar_unpack_weights_w4.argtypes = [vp, i64, i64, vp, vp, vp]
     lib.quasar_w4_linear.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp]
     lib.quasar_w4_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, sz, vp]
+    lib.quasar_drafter_create.argtypes = [ci, ci, i64]
+    lib.quasar_drafter_create.restype = vp
+    lib.quasar_drafter_destroy.argtypes = [vp]
+    lib.quasar_drafter_destroy.restype = None
+    lib.quasar_drafter_append.argtypes = [vp, vp, i64]
+    lib.quasar_drafter_length.argtypes = [vp]
+    lib.quasar_drafter_length.restype = i64
+    lib.quasar_drafter_propose.argtypes = [vp, i64, vp, vp, vp]
     lib.quasar_quantize_weights_smoothed.argtypes = [vp, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.quasar_quantize_activations.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
     lib.quasar_w8a8_linear.argtypes = [vp, i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, sz, vp]
@@ -393,6 +403,43 @@ def w4_lmhead_verify(hidden: torch.Tensor, w4_packed: torch.Tensor, V: int, draf
                                         _ptr(out_accept), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream()))
     return out_argmax, out_accept
+
+
+class Drafter:
+    """Prompt-lookup n-gram drafter (host side): append() tokens as they are accepted, propose() a draft."""
+
+    def __init__(self, k_min: int = 1, k_max: int = 4, capacity_hint: int = 0):
+        self._h = _lib.quasar_drafter_create(k_min, k_max, capacity_hint)
+        if not self._h:
+            raise QuasarError("quasar_drafter_create", -1, "invalid lookup range or out of memory")
+
+    def append(self, tokens) -> None:
+        import numpy as np
+        a = np.ascontiguousarray(tokens, dtype=np.int32).reshape(-1)
+        _check("quasar_drafter_append", _lib.quasar_drafter_append(self._h, a.ctypes.data, a.size))
+
+    def __len__(self) -> int:
+        return int(_lib.quasar_drafter_length(self._h))
+
+    def propose(self, gamma: int):
+        """-> (draft tokens as a list, lookup length that matched or 0)."""
+        buf = (ctypes.c_int32 * max(int(gamma), 1))()
+        n = ctypes.c_int64(0)
+        k = ctypes.c_int(0)
+        _check("quasar_drafter_propose",
+               _lib.quasar_drafter_propose(self._h, gamma, buf, ctypes.byref(n), ctypes.byref(k)))
+        return list(buf[:n.value]), k.value
+
+    def close(self) -> None:
+        if self._h:
+            _lib.quasar_drafter_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def make_workspace(M: int, N: int, K: int, device="cuda") -> torch.Tensor:

@@ -18,6 +18,7 @@
 #include "sample.hpp"
 #include "stream_w8a8.hpp"
 #include "stream_w4.hpp"
+#include "drafter.hpp"
 
 using namespace quasar;
 
@@ -1053,5 +1054,44 @@ int quasar_w4_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
+
+/* ---- prompt-lookup n-gram drafter (host side) ---- */
+
+struct quasar_drafter {
+    NgramDrafter impl;
+    quasar_drafter(int k_min, int k_max, int64_t cap) : impl(k_min, k_max, cap) {}
+};
+
+quasar_drafter *quasar_drafter_create(int k_min, int k_max, int64_t capacity_hint) {
+    if (k_min < 1 || k_max < k_min || k_max > 64 || capacity_hint < 0) return nullptr;
+    try {
+        return new quasar_drafter(k_min, k_max, capacity_hint);
+    } catch (...) {
+        return nullptr;
+    }
+}
+
+void quasar_drafter_destroy(quasar_drafter *d) { delete d; }
+
+int quasar_drafter_append(quasar_drafter *d, const int32_t *tokens, int64_t n) {
+    if (!d || (n > 0 && !tokens)) return QUASAR_ERR_NULL;
+    if (n < 0 || d->impl.length() + n > (int64_t(1) << 31)) return QUASAR_ERR_SHAPE;
+    try {
+        d->impl.append(tokens, n);
+    } catch (...) {
+        return QUASAR_ERR_WORKSPACE;
+    }
+    return QUASAR_OK;
+}
+
+int64_t quasar_drafter_length(const quasar_drafter *d) { return d ? d->impl.length() : -1; }
+
+int quasar_drafter_propose(const quasar_drafter *d, int64_t gamma, int32_t *out_draft, int64_t *out_n_draft,
+                           int *out_lookup_len) {
+    if (!d || !out_draft || !out_n_draft) return QUASAR_ERR_NULL;
+    if (gamma < 1) return QUASAR_ERR_SHAPE;
+    *out_n_draft = d->impl.propose(gamma, out_draft, out_lookup_len);
+    return QUASAR_OK;
+}
 
 }  // extern "C"
