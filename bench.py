@@ -40,6 +40,8 @@ def main() -> int:
                     "and the pure read stream (stderr)")
     ap.add_argument("--detail32", action="store_true", help="also time the Qwen3-32B layer shapes cold at "
                     "M = 8, 16, 32 (both forms of the linear)")
+    ap.add_argument("--detail-layer", action="store_true", help="also time a decoder block (attention excluded) as "
+                    "four fused calls: norm+qkv, o+residual, norm+gate/up, swiglu+down+residual")
     ap.add_argument("--detail4", action="store_true", help="also time the 4-bit group-wise weight form: every layer "
                     "shape cold and the vocabulary verify, for each launch shape of the kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -445,6 +447,53 @@ def main() -> int:
     detail["drafter_us_per_proposal"] = t_prop * 1e6
     detail["drafter_ns_per_appended_token"] = t_app * 1e9
     drafter.close()
+
+    if args.detail_layer:
+        # A decoder block minus attention as four fused calls, chained through all 36 layers' own weights
+        # (cold by construction): RMSNorm -> q/k/v (one 6144-row matrix), o_proj + residual, RMSNorm ->
+        # gate/up with the SwiGLU product in the epilogue (one row-interleaved 24576-row matrix), down_proj +
+        # residual.  The attention output is stood in for by the first 4096 columns of the q/k/v result.
+        I = 12288
+        fused = []
+        for lin in layers:
+            d = {name: (wq, sc) for name, K, N, wq, sc, wp in lin}
+            tg = I // 16
+            wgu = torch.stack([d["gate_proj"][0].view(tg, -1), d["up_proj"][0].view(tg, -1)], dim=1).reshape(-1)
+            sgu = torch.stack([d["gate_proj"][1].view(tg, 16), d["up_proj"][1].view(tg, 16)], dim=1).reshape(-1)
+            fused.append((torch.cat([d["q_proj"][0], d["k_proj"][0], d["v_proj"][0]]),
+                          torch.cat([d["q_proj"][1], d["k_proj"][1], d["v_proj"][1]]),
+                          d["o_proj"][0], d["o_proj"][1], wgu, sgu, d["down_proj"][0], d["down_proj"][1]))
+        gam = torch.ones(H, dtype=torch.bfloat16, device=dev)
+        hid = torch.empty((M, H), dtype=torch.bfloat16, device=dev)
+        qkv = torch.empty((M, 6144), dtype=torch.bfloat16, device=dev)
+        act = torch.empty((M, I), dtype=torch.bfloat16, device=dev)
+
+        def block_step():
+            hid.copy_(h0)
+            for wqkv, sqkv, wo, so, wgu, sgu, wd, sd in fused:
+                qb.w8_linear_fused(hid, wqkv, sqkv, 6144, gamma=gam, eps=1e-6, y=qkv)
+                qb.w8_linear_fused(qkv[:, :H], wo, so, H, residual=hid, y=hid)
+                qb.w8_gateup_swiglu(hid, wgu, sgu, I, gamma=gam, eps=1e-6, y=act)
+                qb.w8_linear_fused(act, wd, sd, H, residual=hid, y=hid)
+        block_step()
+        torch.cuda.synchronize()
+        assert torch.isfinite(hid.float()).all()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            block_step()
+        e1.record()
+        torch.cuda.synchronize()
+        us_blocks = e0.elapsed_time(e1) * 1e3 / 3
+        layer_w = sum(N * K for _, K, N in shapes)
+        log(f"  {L} decoder blocks (attention excluded) as {4 * L} fused calls: {us_blocks:.1f} us = {us_blocks / L:.2f} us per "
+            f"block, {L * layer_w / us_blocks / 1e3:.1f} GB/s of int8 weights ({L * layer_w / us_blocks / 1e3 / HBM_PEAK_GBPS:.1%} "
+            f"of peak); the same weights as {7 * L} plain linear calls without the norm, gate and residual work: see "
+            f"separate_calls_us_per_step under --detail")
+        detail["fused_blocks_us"] = us_blocks
+        detail["fused_block_us_per_layer"] = us_blocks / L
+        del fused
 
     if args.detail4:
         # 4-bit group-wise weights (0.5 B per weight + 2 B per row and group of 128): the layer shapes cold

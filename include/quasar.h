@@ -343,6 +343,40 @@ int quasar_w4_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * ---- The int8 linears with the decoder block's surrounding operations fused in (the rest of
+ * the verification forward around the quantised matmuls of Sec. 3.3: the paper changes the
+ * linears only, the block is the target model's own) ----
+ *
+ * Every rounding to bf16 sits where a bf16 implementation of the block has one; arithmetic
+ * inside is fp32.  The linears are quasar_w8_linear's (same packed weights, same tolerance).
+ *
+ * quasar_w8_linear_fused:    y = [residual +] W8( [RMSNorm](x) )
+ *   gamma     device [K] bf16, 16-byte aligned, or NULL (no normalisation).  With gamma the kernel
+ *             stages bf16( gamma[k] * bf16( x[m,k] * rsqrt(mean_k x[m,:]^2 + eps) ) ) instead of x, so the
+ *             normalised activations never travel through HBM; eps in [0, 1)
+ *   residual  device [M, N] bf16, row stride ldr, or NULL; if given, y = bf16( bf16(linear) + residual ),
+ *             and y may be the residual buffer itself
+ *   other arguments, alignment and errors as quasar_w8_linear (K is never split across workgroups)
+ *
+ * quasar_w8_gateup_swiglu:   y[M, I] = bf16( bf16(silu(gate)) * up ),  gate / up = bf16( W8_gate/up( [RMSNorm](x) ) ),
+ *   silu(g) = g / (1 + exp(-g)).  The two projections share ONE weight matrix of 2 I rows whose rows
+ *   alternate in blocks of 16: rows 32 t .. 32 t + 15 are gate rows 16 t .. 16 t + 15, rows 32 t + 16 .. 32 t + 31
+ *   the up rows of the same indices (quantise that matrix with quasar_quantize_weights; per-row step
+ *   sizes are unaffected by the order).  The gated product is formed in the epilogue of the kernel:
+ *   the projections themselves never travel through HBM.  I a multiple of 16; y row stride ldy >= I,
+ *   a multiple of 4; other arguments as above.
+ */
+int quasar_w8_linear_fused(const uint16_t *x, int64_t M, int64_t K, int64_t ldx,
+                           const uint16_t *gamma, float eps,
+                           const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t N,
+                           const uint16_t *residual, int64_t ldr,
+                           uint16_t *y, int64_t ldy, void *hip_stream);
+int quasar_w8_gateup_swiglu(const uint16_t *x, int64_t M, int64_t K, int64_t ldx,
+                            const uint16_t *gamma, float eps,
+                            const int8_t *wq_packed_interleaved, const uint16_t *scales_bf16_interleaved,
+                            int64_t I, uint16_t *y, int64_t ldy, void *hip_stream);
+
+/*
  * ---- Prompt-lookup n-gram drafter (Sec. 2: drafts by n-gram matching against the context;
  * Sec. 4 "Implementation Details": lookup length adjusted dynamically between a minimum and a
  * maximum, 1 and 4 in the paper; Sec. 4.4: range (K_min, K_max), gamma speculative tokens) ----

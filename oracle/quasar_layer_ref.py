@@ -11,7 +11,10 @@ operations next to the linears are:
 * ``rmsnorm``    x^[m, k] = bf16( gamma[k] * bf16( x[m, k] * r_m ) ),  r_m = 1 / sqrt(mean_k x[m, :]^2 + eps)
 * ``swiglu``     a[m, k]  = bf16( bf16( silu(g[m, k]) ) * u[m, k] ),   silu(g) = g / (1 + exp(-g))
 * ``residual``   y        = bf16( bf16(linear) + residual )
-* ``fused_linear``  the int8 linear (Eq. 8, Eq. 10) applied to one of the above, plus the residual.
+* ``fused_linear``   the int8 linear (Eq. 8, Eq. 10) on the (optionally normalised) activations, plus
+                     the residual.
+* ``gateup_swiglu``  the gate and up projections (two int8 linears on the same, optionally normalised,
+                     activations, each rounded to bf16 as a separate linear is) combined by ``swiglu``.
 
 bf16 values travel as uint16 bit patterns.
 """
@@ -47,19 +50,21 @@ def swiglu(gate_bits, up_bits) -> np.ndarray:
     return _round_bf16(a * u)
 
 
-def fused_linear(x_bits, q, s_bits, *, gamma_bits=None, eps: float = 1e-6, up_bits=None, residual_bits=None):
-    """y = [residual +] W8(pre(x)) -> uint16 bf16 bits [M, N]."""
-    if gamma_bits is not None and up_bits is not None:
-        raise ValueError("one pre-operation at most")
-    a = x_bits
-    if gamma_bits is not None:
-        a = rmsnorm(x_bits, gamma_bits, eps)
-    elif up_bits is not None:
-        a = swiglu(x_bits, up_bits)
+def fused_linear(x_bits, q, s_bits, *, gamma_bits=None, eps: float = 1e-6, residual_bits=None):
+    """y = [residual +] W8([rmsnorm](x)) -> uint16 bf16 bits [M, N]."""
+    a = x_bits if gamma_bits is None else rmsnorm(x_bits, gamma_bits, eps)
     lin = _round_bf16(ref.w8_linear(a, q, s_bits))
     if residual_bits is None:
         return lin
     return _round_bf16(ref.bf16_bits_to_f64(lin) + ref.bf16_bits_to_f64(residual_bits))
+
+
+def gateup_swiglu(x_bits, q_gate, s_gate, q_up, s_up, *, gamma_bits=None, eps: float = 1e-6):
+    """a = swiglu( W8_gate([rmsnorm](x)), W8_up([rmsnorm](x)) ) -> uint16 bf16 bits [M, I]."""
+    a = x_bits if gamma_bits is None else rmsnorm(x_bits, gamma_bits, eps)
+    gate = _round_bf16(ref.w8_linear(a, q_gate, s_gate))
+    up = _round_bf16(ref.w8_linear(a, q_up, s_up))
+    return swiglu(gate, up)
 
 
 def _round_bf16(a) -> np.ndarray:

@@ -34,6 +34,7 @@ EXPORTS = (
     "quasar_w4_lmhead_verify",
     "quasar_drafter_create", "quasar_drafter_destroy", "quasar_drafter_append", "quasar_drafter_length",
     "quasar_drafter_propose",
+    "quasar_w8_linear_fused", "quasar_w8_gateup_swiglu",
 )
 
 
@@ -107,6 +108,8 @@ def _load() -> ctypes.CDLL:
     lib.quasar_unpack_weights_w4.argtypes = [vp, i64, i64, vp, vp, vp]
     lib.quasar_w4_linear.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp]
     lib.quasar_w4_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, sz, vp]
+    lib.quasar_w8_linear_fused.argtypes = [vp, i64, i64, i64, vp, ctypes.c_float, vp, vp, i64, vp, i64, vp, i64, vp]
+    lib.quasar_w8_gateup_swiglu.argtypes = [vp, i64, i64, i64, vp, ctypes.c_float, vp, vp, i64, vp, i64, vp]
     lib.quasar_drafter_create.argtypes = [ci, ci, i64]
     lib.quasar_drafter_create.restype = vp
     lib.quasar_drafter_destroy.argtypes = [vp]
@@ -403,6 +406,61 @@ def w4_lmhead_verify(hidden: torch.Tensor, w4_packed: torch.Tensor, V: int, draf
                                         _ptr(out_accept), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream()))
     return out_argmax, out_accept
+
+
+def _gamma_arg(gamma, K):
+    if gamma is None:
+        return None
+    _dev(gamma, "gamma", torch.bfloat16)
+    if gamma.numel() != K or not gamma.is_contiguous():
+        raise ValueError("gamma must be a contiguous [K] vector")
+    return gamma
+
+
+def w8_linear_fused(x: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Tensor, N: int, *, gamma: torch.Tensor = None,
+                    eps: float = 1e-6, residual: torch.Tensor = None, y: torch.Tensor = None) -> torch.Tensor:
+    """y = [residual +] W8([RMSNorm](x)); the normalisation (gamma, eps) and the residual are optional."""
+    _dev(x, "x", torch.bfloat16)
+    _dev(wq_packed, "wq_packed", torch.int8)
+    _dev(scales, "scales", torch.bfloat16)
+    M, K = x.shape
+    gamma = _gamma_arg(gamma, K)
+    if residual is not None:
+        _dev(residual, "residual", torch.bfloat16)
+        if residual.shape != (M, N) or residual.stride(1) != 1:
+            raise ValueError("residual must be [M, N] with a contiguous last dimension")
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _check("quasar_w8_linear_fused",
+           _lib.quasar_w8_linear_fused(_ptr(x), M, K, x.stride(0), _ptr(gamma), eps, _ptr(wq_packed), _ptr(scales), N,
+                                       _ptr(residual), 0 if residual is None else residual.stride(0),
+                                       _ptr(y), y.stride(0), _stream()))
+    return y
+
+
+def interleave_gate_up(gate: torch.Tensor, up: torch.Tensor) -> torch.Tensor:
+    """[I, K] gate and up weights -> the [2 I, K] matrix quasar_w8_gateup_swiglu expects (rows alternate in
+    blocks of 16: gate rows 16 t .. 16 t + 15, then the up rows of the same indices).  Data movement only."""
+    I, K = gate.shape
+    if up.shape != gate.shape or I % 16:
+        raise ValueError("gate and up must have the same [I, K] shape with I a multiple of 16")
+    return torch.stack([gate.reshape(I // 16, 16, K), up.reshape(I // 16, 16, K)], dim=1).reshape(2 * I, K)
+
+
+def w8_gateup_swiglu(x: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Tensor, I: int, *, gamma: torch.Tensor = None,
+                     eps: float = 1e-6, y: torch.Tensor = None) -> torch.Tensor:
+    """y[M, I] = silu(gate) * up with both projections taken from the row-interleaved [2 I, K] int8 matrix."""
+    _dev(x, "x", torch.bfloat16)
+    _dev(wq_packed, "wq_packed", torch.int8)
+    _dev(scales, "scales", torch.bfloat16)
+    M, K = x.shape
+    gamma = _gamma_arg(gamma, K)
+    if y is None:
+        y = torch.empty((M, I), dtype=torch.bfloat16, device=x.device)
+    _check("quasar_w8_gateup_swiglu",
+           _lib.quasar_w8_gateup_swiglu(_ptr(x), M, K, x.stride(0), _ptr(gamma), eps, _ptr(wq_packed), _ptr(scales), I,
+                                        _ptr(y), y.stride(0), _stream()))
+    return y
 
 
 class Drafter:

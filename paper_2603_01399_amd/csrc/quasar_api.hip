@@ -537,6 +537,40 @@ int launch_w8a8(const GemmParams &base, int M, hipStream_t stream, int *grid_out
     return launch(stream_w8a8_kernel<32, EPI, 16, 8>, pl.grid, 1024, lds, stream, p);
 }
 
+// The int8 linear with the block's surrounding operations fused in: default launch shape, K in
+// chunks when the activations do not fit the LDS (no split across workgroups).  The gate/up form
+// hands tiles out in pairs and keeps NB KB of the scale region for the gate tile of a pair.
+template <int EPI, int PRE, bool RES>
+int launch_fused(const GemmParams &base, int M, hipStream_t stream) {
+    GemmParams p = base;
+    p.Srow = p.S;
+    p.ksplit = 1;
+    const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
+    const int NB = MP == 32 ? 2 : 1;
+    Plan pl = make_plan(p.T, p.S, 128 * MP, NB * 1024, 16, true);
+    int lds = pl.lds_bytes;
+    int sc_bytes = pl.sc_bytes;
+    if (EPI == EPI_SWIGLU) {
+        // whole pairs per workgroup: up to one tile more than an even split, and the kept gate tile
+        const int pairs = p.T / 2;
+        if (pl.grid > pairs) pl.grid = pairs;
+        const int tpw = 2 * ((pairs + pl.grid - 1) / pl.grid);
+        sc_bytes = ((tpw * kTileRows * 2 + 15) / 16) * 16 + NB * 1024;
+        lds = pl.xs_bytes + sc_bytes + 2 * 16 * NB * 1024 + (pl.C > 1 ? tpw * NB * 1024 : 0);
+        if (lds < kMinLds) lds = kMinLds;
+    }
+    if (pl.grid > kMaxGrid || pl.grid < 1 || lds > kMaxLds) return QUASAR_ERR_SHAPE;
+    p.SC = pl.SC;
+    p.C = pl.C;
+    p.xs_bytes = pl.xs_bytes;
+    p.sc_bytes = sc_bytes;
+    if (MP == 8)
+        return launch(stream_mfma_kernel<8, false, EPI, 16, 4, PRE, RES>, pl.grid, 1024, lds, stream, p);
+    if (MP == 16)
+        return launch(stream_mfma_kernel<16, false, EPI, 16, 4, PRE, RES>, pl.grid, 1024, lds, stream, p);
+    return launch(stream_mfma_kernel<32, false, EPI, 16, 4, PRE, RES>, pl.grid, 1024, lds, stream, p);
+}
+
 std::atomic<int> g_w4_nw{16};
 std::atomic<int> g_w4_d{2};
 
@@ -1054,6 +1088,57 @@ int quasar_w4_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
+
+/* ---- int8 linears with the decoder block's surrounding operations fused in ---- */
+
+int quasar_w8_linear_fused(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const uint16_t *gamma, float eps,
+                           const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t N, const uint16_t *residual,
+                           int64_t ldr, uint16_t *y, int64_t ldy, void *hip_stream) {
+    if (!x || !wq_packed || !scales_bf16 || !y) return QUASAR_ERR_NULL;
+    if (const int e = check_mnk(M, N, K)) return e;
+    if (ldx < K || ldy < N || ldx % 8 || ldy % 8) return QUASAR_ERR_SHAPE;
+    if (gamma && !(eps >= 0.f && eps < 1.0f)) return QUASAR_ERR_SHAPE;
+    if (residual && (ldr < N || ldr % 4)) return QUASAR_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(wq_packed, 16) || !aligned(scales_bf16, 8) ||
+        !aligned(gamma, 16) || !aligned(residual, 8))
+        return QUASAR_ERR_ALIGN;
+    GemmParams p{};
+    p.x = x; p.ldx = ldx; p.w = reinterpret_cast<const u32x4 *>(wq_packed); p.scales = scales_bf16;
+    p.y = y; p.ldy = ldy; p.partial = nullptr;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.T = (int)(N / kTileRows);
+    p.S = (int)(K / kStepK8);
+    p.pre_arg = gamma; p.eps = eps; p.resid = residual; p.ldr = ldr;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int m = (int)M;
+    if (gamma)
+        return residual ? launch_fused<EPI_LINEAR, PRE_RMSNORM, true>(p, m, st)
+                        : launch_fused<EPI_LINEAR, PRE_RMSNORM, false>(p, m, st);
+    return residual ? launch_fused<EPI_LINEAR, PRE_NONE, true>(p, m, st)
+                    : launch_fused<EPI_LINEAR, PRE_NONE, false>(p, m, st);
+}
+
+int quasar_w8_gateup_swiglu(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const uint16_t *gamma, float eps,
+                            const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t I, uint16_t *y, int64_t ldy,
+                            void *hip_stream) {
+    if (!x || !wq_packed || !scales_bf16 || !y) return QUASAR_ERR_NULL;
+    if (I < 16 || I % 16 || I > (1 << 25)) return QUASAR_ERR_SHAPE;
+    if (const int e = check_mnk(M, 2 * I, K)) return e;
+    if (ldx < K || ldy < I || ldx % 8 || ldy % 4) return QUASAR_ERR_SHAPE;
+    if (gamma && !(eps >= 0.f && eps < 1.0f)) return QUASAR_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(y, 8) || !aligned(wq_packed, 16) || !aligned(scales_bf16, 8) || !aligned(gamma, 16))
+        return QUASAR_ERR_ALIGN;
+    GemmParams p{};
+    p.x = x; p.ldx = ldx; p.w = reinterpret_cast<const u32x4 *>(wq_packed); p.scales = scales_bf16;
+    p.y = y; p.ldy = ldy; p.partial = nullptr;
+    p.M = (int)M; p.N = (int)(2 * I); p.K = (int)K;
+    p.T = (int)(2 * I / kTileRows);
+    p.S = (int)(K / kStepK8);
+    p.pre_arg = gamma; p.eps = eps;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    return gamma ? launch_fused<EPI_SWIGLU, PRE_RMSNORM, false>(p, (int)M, st)
+                 : launch_fused<EPI_SWIGLU, PRE_NONE, false>(p, (int)M, st);
+}
 
 /* ---- prompt-lookup n-gram drafter (host side) ---- */
 

@@ -36,11 +36,53 @@ struct GemmParams {
     int ksplit;
     int slice_steps;
     float *part32;
+    // fused operations around the linear (stream_mfma_kernel with PRE / RES):
+    const uint16_t *pre_arg;   // PRE_RMSNORM: gamma [K] bf16
+    float eps;                 // PRE_RMSNORM
+    const uint16_t *resid;     // RES: residual [M, N] bf16, row stride ldr (may be y itself)
+    long long ldr;
 };
 
+// Operation applied to the activations while they are staged (the normalisation in front of
+// the linears of a decoder block, fused into the linear that consumes its result):
+//   PRE_RMSNORM  x^ = bf16( gamma * bf16( x * rsqrt(mean_k x^2 + eps) ) )      (fp32 inside)
+// with the bf16 roundings where a bf16 implementation of the block has them.
+enum { PRE_NONE = 0, PRE_RMSNORM = 1 };
+
+__device__ __forceinline__ u32x4 pre_rmsnorm_piece(const u32x4 x, const u32x4 gamma, float r) {
+    const unsigned int xw[4] = {x.x, x.y, x.z, x.w}, gw[4] = {gamma.x, gamma.y, gamma.z, gamma.w};
+    unsigned int o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float lo = bf16_bits_to_float(float_to_bf16_bits(bf16_bits_to_float(xw[i] & 0xFFFFu) * r));
+        const float hi = bf16_bits_to_float(float_to_bf16_bits(__uint_as_float(xw[i] & 0xFFFF0000u) * r));
+        o[i] = float_to_bf16_bits(lo * bf16_bits_to_float(gw[i] & 0xFFFFu)) |
+               (float_to_bf16_bits(hi * __uint_as_float(gw[i] & 0xFFFF0000u)) << 16);
+    }
+    return u32x4{o[0], o[1], o[2], o[3]};
+}
+__device__ __forceinline__ float silu_bf16(float g) {
+    return bf16_bits_to_float(float_to_bf16_bits(__fdiv_rn(g, 1.0f + __expf(-g))));
+}
+__device__ __forceinline__ float piece_sumsq(const u32x4 x) {
+    const unsigned int xw[4] = {x.x, x.y, x.z, x.w};
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float lo = bf16_bits_to_float(xw[i] & 0xFFFFu), hi = __uint_as_float(xw[i] & 0xFFFF0000u);
+        s = __builtin_fmaf(lo, lo, s);
+        s = __builtin_fmaf(hi, hi, s);
+    }
+    return s;
+}
+
 // EPI_LOGITS: the linear epilogue with fp32 outputs, part32[m][n] (row stride N): the input of
-// the stochastic verification
-enum { EPI_LINEAR = 0, EPI_ARGMAX = 1, EPI_LOGITS = 2 };
+// the stochastic verification.
+// EPI_SWIGLU: the weight rows alternate in blocks of 16 between the gate and the up projection
+// (tile 2t = gate rows 16t.., tile 2t+1 = up rows 16t..); the epilogue of an up tile combines it
+// with the gate tile before it, y[m][16t + r] = bf16( bf16(silu(bf16(gate))) * bf16(up) ), so the
+// two projections never travel through HBM.  Workgroups own whole tile pairs.
+enum { EPI_LINEAR = 0, EPI_ARGMAX = 1, EPI_LOGITS = 2, EPI_SWIGLU = 3 };
 
 // ------------------------------------------------------------------------------------
 // Per-wave walk over the workgroup's (chunk, tile, step) sequence with a ring of D loads.
@@ -127,7 +169,7 @@ struct WaveWalk {
 // meanwhile.  With a workspace the host instead splits K across workgroups (ksplit slices):
 // a workgroup stages only its slice of x, once, and writes fp32 partial tiles that
 // splitk_finalize_kernel sums in slice order.
-template <int MP, bool W16, int EPI, int NW, int D>
+template <int MP, bool W16, int EPI, int NW, int D, int PRE = PRE_NONE, bool RES = false>
 __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p0) {
     extern __shared__ __align__(16) unsigned char lds[];
     GemmParams p = p0;
@@ -147,7 +189,9 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
     constexpr int PPS = W16 ? 4 : 8;         // 16-byte activation pieces (8 k) per step
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
     constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
-    constexpr int XB = 8;                    // activation pieces per thread per batch
+    // activation pieces per thread per batch (the fused staging operations hold a second
+    // operand per piece: half the batch keeps the register count of the plain kernel)
+    constexpr int XB = PRE == PRE_NONE ? 8 : 4;
     constexpr int nthreads = NW * 64;
 
     const int tid = threadIdx.x;
@@ -155,15 +199,16 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, mcol = lane & 15;
 
-    
-    const int t0 = (int)(((long long)p.T * b) / G);
-    const int t1 = (int)(((long long)p.T * (b + 1)) / G);
+    constexpr int TU = EPI == EPI_SWIGLU ? 2 : 1;   // tiles are handed out in units of TU
+    const int t0 = TU * (int)(((long long)(p.T / TU) * b) / G);
+    const int t1 = TU * (int)(((long long)(p.T / TU) * (b + 1)) / G);
     const int ntiles = t1 - t0;
 
     u32x4 *xs = reinterpret_cast<u32x4 *>(lds);                                   // [SC*PPS][MP]
     uint16_t *sc_lds = reinterpret_cast<uint16_t *>(lds + p.xs_bytes);            // [tpw*16]
     f32x4 *stage = reinterpret_cast<f32x4 *>(lds + p.xs_bytes + p.sc_bytes);      // [2][NW][NB][64]
     f32x4 *accs = stage + 2 * NW * NB * 64;                                       // [ntiles][NB][64] (C > 1)
+    f32x4 *gate_keep = stage - NB * 64;   // EPI_SWIGLU: the last NB KB of the scale region, [NB][64]
 
     auto x_piece_load = [&](int c, int idx) -> u32x4 {
         const int scc = min(p.SC, p.S - c * p.SC);
@@ -178,6 +223,25 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
         }
         return v;
     };
+    // second operand of the fused staging operation for the same piece: gamma[k .. k+7]
+    auto aux_piece_load = [&](int c, int idx) -> u32x4 {
+        const int scc = min(p.SC, p.S - c * p.SC);
+        const int npieces = scc * PPS * MP;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if constexpr (PRE != PRE_NONE) {
+            if (idx < npieces) {
+                const int p8 = idx >> LMP;
+                const long long k = (long long)c * p.SC * KSTEP + 8ll * p8;
+                v = *reinterpret_cast<const u32x4 *>(p.pre_arg + k);
+            }
+        }
+        return v;
+    };
+    float r_own = 1.f;   // PRE_RMSNORM: rsqrt(mean x^2 + eps) of the token this thread stages
+    auto pre_apply = [&](const u32x4 x, const u32x4 aux) -> u32x4 {
+        if constexpr (PRE == PRE_RMSNORM) return pre_rmsnorm_piece(x, aux, r_own);
+        else return x;
+    };
     auto x_stage = [&](int c, int first_batch) {
         const int scc = min(p.SC, p.S - c * p.SC);
         const int npieces = scc * PPS * MP;
@@ -185,6 +249,13 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
             u32x4 v[XB];
 #pragma unroll
             for (int i = 0; i < XB; ++i) v[i] = x_piece_load(c, base + i * nthreads + tid);
+            if constexpr (PRE != PRE_NONE) {
+                u32x4 a[XB];
+#pragma unroll
+                for (int i = 0; i < XB; ++i) a[i] = aux_piece_load(c, base + i * nthreads + tid);
+#pragma unroll
+                for (int i = 0; i < XB; ++i) v[i] = pre_apply(v[i], a[i]);
+            }
 #pragma unroll
             for (int i = 0; i < XB; ++i) {
                 const int idx = base + i * nthreads + tid;
@@ -201,6 +272,11 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
     u32x4 xfirst[XB];
 #pragma unroll
     for (int i = 0; i < XB; ++i) xfirst[i] = x_piece_load(0, i * nthreads + tid);
+    u32x4 afirst[PRE != PRE_NONE ? XB : 1];
+    if constexpr (PRE != PRE_NONE) {
+#pragma unroll
+        for (int i = 0; i < XB; ++i) afirst[i] = aux_piece_load(0, i * nthreads + tid);
+    }
     unsigned int sc_first = 0;
     if constexpr (!W16) {
         if (2 * tid < ntiles * kTileRows)
@@ -212,12 +288,57 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
         ring[d] = ring_refill(walk.addr(ld), u32x4{0u, 0u, 0u, 0u});
         walk.advance(ld);
     }
+    if constexpr (PRE == PRE_RMSNORM) {
+        // sum of squares of this thread's token over the whole K: the first batch is in
+        // registers, the rest is read here; then a fixed-order sum over the threads of a token
+        const int m_own = tid & (MP - 1);
+        const int npieces0 = min(p.SC, p.S) * PPS * MP;
+        const int npieces_all = p.S * PPS * MP;
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < XB; ++i)
+            if (i * nthreads + tid < npieces0) ss += piece_sumsq(xfirst[i]);
+        // pieces of chunk 0 beyond the first batch and of the later chunks (same index space:
+        // piece p8 of token m sits at idx = p8 * MP + m whatever the chunking)
+        for (int base = 0; base < npieces_all; base += nthreads * XB) {
+            u32x4 v[XB];
+#pragma unroll
+            for (int i = 0; i < XB; ++i) {
+                const int idx = base + i * nthreads + tid;
+                v[i] = u32x4{0u, 0u, 0u, 0u};
+                const bool held = base == 0 && idx < npieces0;
+                if (!held && idx < npieces_all && m_own < p.M)
+                    v[i] = *reinterpret_cast<const u32x4 *>(p.x + m_own * p.ldx + 8ll * (idx >> LMP));
+            }
+#pragma unroll
+            for (int i = 0; i < XB; ++i) ss += piece_sumsq(v[i]);
+        }
+        float *red = reinterpret_cast<float *>(stage);           // [nthreads], then [16 * MP]
+        red[tid] = ss;
+        lds_barrier();
+        if (tid < 16 * MP) {
+            const int j = tid >> LMP;
+            float a = 0.f;
+            for (int q = j; q < nthreads / MP; q += 16) a += red[q * MP + m_own];
+            red[nthreads + tid] = a;
+        }
+        lds_barrier();
+        float tot = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) tot += red[nthreads + j * MP + m_own];
+        r_own = __fdiv_rn(1.0f, __fsqrt_rn(__fdiv_rn(tot, (float)p.K) + p.eps));
+        // the staging loads above are conditional: start the main loop from a known-empty queue
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
     {
         const int npieces = min(p.SC, p.S) * PPS * MP;
 #pragma unroll
         for (int i = 0; i < XB; ++i) {
             const int idx = i * nthreads + tid;
-            if (idx < npieces) xs[idx] = xfirst[i];
+            if (idx < npieces) {
+                if constexpr (PRE != PRE_NONE) xs[idx] = pre_apply(xfirst[i], afirst[i]);
+                else xs[idx] = xfirst[i];
+            }
         }
         if constexpr (!W16) {
             if (2 * tid < ntiles * kTileRows) reinterpret_cast<unsigned int *>(sc_lds)[tid] = sc_first;
@@ -325,7 +446,22 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                                 const int m = mcol + 16 * nb;
                                 const float v0 = rsum[nb].x * s4[0], v1 = rsum[nb].y * s4[1];
                                 const float v2 = rsum[nb].z * s4[2], v3 = rsum[nb].w * s4[3];
-                                if constexpr (EPI == EPI_LOGITS) {
+                                if constexpr (EPI == EPI_SWIGLU) {
+                                    // both projections are rounded to bf16 as separate linears would be
+                                    const f32x4 r = {bf16_bits_to_float(float_to_bf16_bits(v0)),
+                                                     bf16_bits_to_float(float_to_bf16_bits(v1)),
+                                                     bf16_bits_to_float(float_to_bf16_bits(v2)),
+                                                     bf16_bits_to_float(float_to_bf16_bits(v3))};
+                                    if (((t0 + tl) & 1) == 0) {
+                                        gate_keep[nb * 64 + lane] = r;      // read by the next tile's reducer, after a barrier
+                                    } else if (m < p.M) {
+                                        const f32x4 gt = gate_keep[nb * 64 + lane];
+                                        u32x2 o;
+                                        o.x = float_to_bf16_bits(silu_bf16(gt.x) * r.x) | (float_to_bf16_bits(silu_bf16(gt.y) * r.y) << 16);
+                                        o.y = float_to_bf16_bits(silu_bf16(gt.z) * r.z) | (float_to_bf16_bits(silu_bf16(gt.w) * r.w) << 16);
+                                        *reinterpret_cast<u32x2 *>(p.y + m * p.ldy + ((t0 + tl) >> 1) * kTileRows + 4 * g) = o;
+                                    }
+                                } else if constexpr (EPI == EPI_LOGITS) {
                                     if (m < p.M)
                                         *reinterpret_cast<f32x4 *>(p0.part32 + (long long)m * p.N + n0) =
                                             f32x4{v0, v1, v2, v3};
@@ -334,6 +470,17 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                                         if (p0.ksplit > 1) {
                                             *reinterpret_cast<f32x4 *>(p0.part32 + ((long long)slice * p.M + m) * p.N + n0) =
                                                 rsum[nb];
+                                        } else if constexpr (RES) {
+                                            // y = bf16( bf16(linear) + residual ), as a bf16 block computes it
+                                            const u32x2 rr = *reinterpret_cast<const u32x2 *>(p.resid + m * p.ldr + n0);
+                                            const float r0 = bf16_bits_to_float(float_to_bf16_bits(v0)) + bf16_bits_to_float(rr.x & 0xFFFFu);
+                                            const float r1 = bf16_bits_to_float(float_to_bf16_bits(v1)) + __uint_as_float(rr.x & 0xFFFF0000u);
+                                            const float r2 = bf16_bits_to_float(float_to_bf16_bits(v2)) + bf16_bits_to_float(rr.y & 0xFFFFu);
+                                            const float r3 = bf16_bits_to_float(float_to_bf16_bits(v3)) + __uint_as_float(rr.y & 0xFFFF0000u);
+                                            u32x2 o;
+                                            o.x = float_to_bf16_bits(r0) | (float_to_bf16_bits(r1) << 16);
+                                            o.y = float_to_bf16_bits(r2) | (float_to_bf16_bits(r3) << 16);
+                                            *reinterpret_cast<u32x2 *>(p.y + m * p.ldy + n0) = o;
                                         } else {
                                             u32x2 o;
                                             o.x = float_to_bf16_bits(v0) | (float_to_bf16_bits(v1) << 16);

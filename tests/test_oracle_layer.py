@@ -84,25 +84,31 @@ def test_swiglu_operand_roles_and_roundings():
         lr.swiglu(gate, up[:, :3])
 
 
-def test_fused_linear_is_the_composition():
+def test_fused_linear_and_gateup_are_the_compositions():
     r = np.random.Generator(np.random.Philox(62))
     M, N, K = 4, 32, 128
     w = (r.standard_normal((N, K)) * 0.02).astype(np.float32)
     q, s = ref.quantize_weights(w)
+    w2 = (r.standard_normal((N, K)) * 0.02).astype(np.float32)
+    q2, s2 = ref.quantize_weights(w2)
     xb = bits(r.standard_normal((M, K)))
-    ub = bits(r.standard_normal((M, K)))
     gb = bits(1.0 + 0.1 * r.standard_normal(K))
     rb = bits(r.standard_normal((M, N)))
     plain = lr.fused_linear(xb, q, s)
     assert np.array_equal(plain, ref.f64_to_bf16_bits(ref.w8_linear(xb, q, s)))
     assert np.array_equal(lr.fused_linear(xb, q, s, gamma_bits=gb, eps=1e-6),
                           ref.f64_to_bf16_bits(ref.w8_linear(lr.rmsnorm(xb, gb, 1e-6), q, s)))
-    assert np.array_equal(lr.fused_linear(xb, q, s, up_bits=ub),
-                          ref.f64_to_bf16_bits(ref.w8_linear(lr.swiglu(xb, ub), q, s)))
     # residual: added after the linear's own rounding; zero weights give the residual back
     res = lr.fused_linear(xb, q, s, residual_bits=rb)
     assert np.array_equal(res, bits(vals(plain) + vals(rb)))
     assert np.array_equal(lr.fused_linear(xb, np.zeros_like(q), s, residual_bits=rb), rb)
     assert np.array_equal(lr.fused_linear(xb, q, s, residual_bits=bits(np.zeros((M, N)))), plain)
-    with pytest.raises(ValueError):
-        lr.fused_linear(xb, q, s, gamma_bits=gb, up_bits=ub)
+    # gate/up: the gate goes through silu, the up projection does not
+    a = lr.gateup_swiglu(xb, q, s, q2, s2)
+    assert np.array_equal(a, lr.swiglu(plain, lr.fused_linear(xb, q2, s2)))
+    assert not np.array_equal(a, lr.gateup_swiglu(xb, q2, s2, q, s))
+    an = lr.gateup_swiglu(xb, q, s, q2, s2, gamma_bits=gb, eps=1e-6)
+    assert np.array_equal(an, lr.swiglu(lr.fused_linear(xb, q, s, gamma_bits=gb), lr.fused_linear(xb, q2, s2, gamma_bits=gb)))
+    # zero up weights give zeros; a zero gate gives zeros as well (silu(0) = 0)
+    assert not lr.gateup_swiglu(xb, q, s, np.zeros_like(q2), s2).any()
+    assert not lr.gateup_swiglu(xb, np.zeros_like(q), s, q2, s2).any()
