@@ -377,6 +377,45 @@ int quasar_w8_gateup_swiglu(const uint16_t *x, int64_t M, int64_t K, int64_t ldx
                             int64_t I, uint16_t *y, int64_t ldy, void *hip_stream);
 
 /*
+ * ---- Attention of a verification step (Sec. 3.1: the gamma + 1 positions are verified in one
+ * forward pass; the attention of that pass is the target model's own: grouped-query attention
+ * with a key/value cache, per-head RMSNorm of queries and keys, rotary position embedding;
+ * head dimension 128) ----
+ *
+ * The key/value cache of a layer is ONE device buffer of quasar_kv_cache_bytes(n_kv_heads, max_len)
+ * bytes, 16-byte aligned, in a layout private to the library (blocks of 32 positions in
+ * matrix-core operand order); it need not be initialised.  Positions are written by
+ * quasar_attn_prepare (the M new positions of a step) or quasar_kv_cache_fill (plain
+ * [n, n_kv_heads, 128] bf16 keys and values, already normalised and rotated, to positions
+ * pos0 .. pos0 + n - 1, e.g. a prompt).
+ *
+ * quasar_attn_prepare: qkv is the fused projection output [M, (n_q_heads + 2 n_kv_heads) * 128] bf16
+ *   (query heads, then key heads, then value heads; row stride ld).  Queries and keys:
+ *   n = bf16( gamma * bf16( x * rsqrt(mean_head x^2 + eps) ) ) per head, then the rotary embedding at
+ *   position L + m in the rotate-half convention with angles (L + m) * rope_theta^(-2 i / 128), one
+ *   rounding to bf16.  Queries go to q_out [M, n_q_heads * 128] (row stride ldq); keys and values
+ *   (values unchanged) into the cache at positions L .. L + M - 1.  L + M <= max_len.
+ *
+ * quasar_verify_attention: out[m, h, :] = softmax_j( q[m, h, :] . k[j, h / G, :] / sqrt(128) ) v[j, h / G, :]
+ *   over the cached positions j <= L_total - M + m (the M queries are the last M cached positions,
+ *   causal among themselves), G = n_q_heads / n_kv_heads, M * G <= 64; probabilities enter the
+ *   second product as bf16, sums are fp32, one rounding of the output to bf16.  q as written by
+ *   quasar_attn_prepare (16-byte aligned, ldq a multiple of 8); out [M, n_q_heads * 128] bf16, row
+ *   stride ldo a multiple of 4; workspace: quasar_attention_workspace_bytes(M, n_q_heads, n_kv_heads, L_total)
+ *   bytes (partial results of the splits over the positions).  Two launches.
+ */
+size_t quasar_kv_cache_bytes(int64_t n_kv_heads, int64_t max_len);   /* 0 on invalid arguments */
+int quasar_kv_cache_fill(const uint16_t *k, const uint16_t *v, int64_t n, int64_t n_kv_heads, int64_t pos0,
+                         void *kv_cache, int64_t max_len, void *hip_stream);
+int quasar_attn_prepare(const uint16_t *qkv, int64_t M, int64_t ld, int64_t n_q_heads, int64_t n_kv_heads,
+                        int64_t L, const uint16_t *q_gamma, const uint16_t *k_gamma, float eps, float rope_theta,
+                        uint16_t *q_out, int64_t ldq, void *kv_cache, int64_t max_len, void *hip_stream);
+size_t quasar_attention_workspace_bytes(int64_t M, int64_t n_q_heads, int64_t n_kv_heads, int64_t L_total);
+int quasar_verify_attention(const uint16_t *q, int64_t M, int64_t ldq, int64_t n_q_heads, int64_t n_kv_heads,
+                            const void *kv_cache, int64_t max_len, int64_t L_total,
+                            uint16_t *out, int64_t ldo, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * ---- Prompt-lookup n-gram drafter (Sec. 2: drafts by n-gram matching against the context;
  * Sec. 4 "Implementation Details": lookup length adjusted dynamically between a minimum and a
  * maximum, 1 and 4 in the paper; Sec. 4.4: range (K_min, K_max), gamma speculative tokens) ----

@@ -35,6 +35,8 @@ EXPORTS = (
     "quasar_drafter_create", "quasar_drafter_destroy", "quasar_drafter_append", "quasar_drafter_length",
     "quasar_drafter_propose",
     "quasar_w8_linear_fused", "quasar_w8_gateup_swiglu",
+    "quasar_kv_cache_bytes", "quasar_kv_cache_fill", "quasar_attn_prepare", "quasar_attention_workspace_bytes",
+    "quasar_verify_attention",
 )
 
 
@@ -110,6 +112,13 @@ def _load() -> ctypes.CDLL:
     lib.quasar_w4_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, sz, vp]
     lib.quasar_w8_linear_fused.argtypes = [vp, i64, i64, i64, vp, ctypes.c_float, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.quasar_w8_gateup_swiglu.argtypes = [vp, i64, i64, i64, vp, ctypes.c_float, vp, vp, i64, vp, i64, vp]
+    lib.quasar_kv_cache_bytes.argtypes = [i64, i64]
+    lib.quasar_kv_cache_bytes.restype = sz
+    lib.quasar_kv_cache_fill.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
+    lib.quasar_attn_prepare.argtypes = [vp, i64, i64, i64, i64, i64, vp, vp, ctypes.c_float, ctypes.c_float, vp, i64, vp, i64, vp]
+    lib.quasar_attention_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    lib.quasar_attention_workspace_bytes.restype = sz
+    lib.quasar_verify_attention.argtypes = [vp, i64, i64, i64, i64, vp, i64, i64, vp, i64, vp, sz, vp]
     lib.quasar_drafter_create.argtypes = [ci, ci, i64]
     lib.quasar_drafter_create.restype = vp
     lib.quasar_drafter_destroy.argtypes = [vp]
@@ -461,6 +470,65 @@ def w8_gateup_swiglu(x: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Ten
            _lib.quasar_w8_gateup_swiglu(_ptr(x), M, K, x.stride(0), _ptr(gamma), eps, _ptr(wq_packed), _ptr(scales), I,
                                         _ptr(y), y.stride(0), _stream()))
     return y
+
+
+class KvCache:
+    """Key/value cache of one layer in the library's layout (head dimension 128)."""
+
+    def __init__(self, n_kv_heads: int, max_len: int, device="cuda"):
+        nbytes = _lib.quasar_kv_cache_bytes(n_kv_heads, max_len)
+        if nbytes == 0:
+            raise ValueError("invalid cache shape")
+        self.n_kv_heads, self.max_len = n_kv_heads, max_len
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+    def fill(self, k: torch.Tensor, v: torch.Tensor, pos0: int = 0) -> None:
+        """k, v: [n, n_kv_heads, 128] bf16 contiguous, already normalised and rotated."""
+        _dev(k, "k", torch.bfloat16)
+        _dev(v, "v", torch.bfloat16)
+        if k.shape != v.shape or k.dim() != 3 or k.shape[1] != self.n_kv_heads or k.shape[2] != 128:
+            raise ValueError("k and v must be [n, n_kv_heads, 128]")
+        k, v = k.contiguous(), v.contiguous()
+        _check("quasar_kv_cache_fill", _lib.quasar_kv_cache_fill(_ptr(k), _ptr(v), k.shape[0], self.n_kv_heads, pos0,
+                                                                  _ptr(self.buf), self.max_len, _stream()))
+
+
+def attn_prepare(qkv: torch.Tensor, n_q_heads: int, cache: KvCache, L: int, q_gamma: torch.Tensor,
+                 k_gamma: torch.Tensor, eps: float = 1e-6, rope_theta: float = 1.0e6, q_out: torch.Tensor = None):
+    """Normalise and rotate the queries and keys of the M new positions, append keys and values at L .. L+M-1."""
+    _dev(qkv, "qkv", torch.bfloat16)
+    _dev(q_gamma, "q_gamma", torch.bfloat16)
+    _dev(k_gamma, "k_gamma", torch.bfloat16)
+    M = qkv.shape[0]
+    if qkv.stride(1) != 1 or q_gamma.numel() != 128 or k_gamma.numel() != 128:
+        raise ValueError("qkv needs a contiguous last dimension; gammas are [128]")
+    if q_out is None:
+        q_out = torch.empty((M, n_q_heads * 128), dtype=torch.bfloat16, device=qkv.device)
+    _check("quasar_attn_prepare",
+           _lib.quasar_attn_prepare(_ptr(qkv), M, qkv.stride(0), n_q_heads, cache.n_kv_heads, L, _ptr(q_gamma),
+                                    _ptr(k_gamma), eps, rope_theta, _ptr(q_out), q_out.stride(0), _ptr(cache.buf),
+                                    cache.max_len, _stream()))
+    return q_out
+
+
+def attention_workspace(M: int, n_q_heads: int, n_kv_heads: int, L_total: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(_lib.quasar_attention_workspace_bytes(M, n_q_heads, n_kv_heads, L_total), 16),
+                       dtype=torch.uint8, device=device)
+
+
+def verify_attention(q: torch.Tensor, n_q_heads: int, cache: KvCache, L_total: int, workspace: torch.Tensor = None,
+                     out: torch.Tensor = None) -> torch.Tensor:
+    _dev(q, "q", torch.bfloat16)
+    M = q.shape[0]
+    if workspace is None:
+        workspace = attention_workspace(M, n_q_heads, cache.n_kv_heads, L_total, q.device)
+    if out is None:
+        out = torch.empty((M, n_q_heads * 128), dtype=torch.bfloat16, device=q.device)
+    _check("quasar_verify_attention",
+           _lib.quasar_verify_attention(_ptr(q), M, q.stride(0), n_q_heads, cache.n_kv_heads, _ptr(cache.buf),
+                                        cache.max_len, L_total, _ptr(out), out.stride(0), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream()))
+    return out
 
 
 class Drafter:

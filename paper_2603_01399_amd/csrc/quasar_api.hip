@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -19,6 +20,7 @@
 #include "stream_w8a8.hpp"
 #include "stream_w4.hpp"
 #include "drafter.hpp"
+#include "attention.hpp"
 
 using namespace quasar;
 
@@ -1138,6 +1140,114 @@ int quasar_w8_gateup_swiglu(const uint16_t *x, int64_t M, int64_t K, int64_t ldx
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     return gamma ? launch_fused<EPI_SWIGLU, PRE_RMSNORM, false>(p, (int)M, st)
                  : launch_fused<EPI_SWIGLU, PRE_NONE, false>(p, (int)M, st);
+}
+
+/* ---- attention of a verification step ---- */
+
+namespace {
+constexpr int kAttnWaves = 4;
+struct AttnShape { int NQT, nblk, nsplit; };
+bool attn_shape(int64_t M, int64_t Hq, int64_t Hkv, int64_t L_total, AttnShape &a) {
+    if (M < 1 || M > 32 || Hkv < 1 || Hkv > 1024 || Hq < Hkv || Hq % Hkv || Hq > 4096) return false;
+    if (L_total < M || L_total > (1 << 24)) return false;
+    const int64_t R = M * (Hq / Hkv);
+    if (R > 64) return false;
+    a.NQT = R <= 32 ? 2 : 4;
+    a.nblk = (int)((L_total + kKvBlock - 1) / kKvBlock);
+    int64_t cap = 2 * (int64_t)device_cus() / Hkv;
+    if (cap < 1) cap = 1;
+    int64_t ns = a.nblk / kAttnWaves;
+    if (ns < 1) ns = 1;
+    a.nsplit = (int)(ns < cap ? ns : cap);
+    return true;
+}
+int64_t cache_blocks(int64_t max_len) { return (max_len + kKvBlock - 1) / kKvBlock; }
+}  // namespace
+
+size_t quasar_kv_cache_bytes(int64_t n_kv_heads, int64_t max_len) {
+    if (n_kv_heads < 1 || n_kv_heads > 1024 || max_len < 1 || max_len > (1 << 24)) return 0;
+    return 2u * (size_t)n_kv_heads * (size_t)cache_blocks(max_len) * (size_t)kKvBlockBytes;
+}
+
+int quasar_kv_cache_fill(const uint16_t *k, const uint16_t *v, int64_t n, int64_t n_kv_heads, int64_t pos0,
+                         void *kv_cache, int64_t max_len, void *hip_stream) {
+    if (!k || !v || !kv_cache) return QUASAR_ERR_NULL;
+    if (!quasar_kv_cache_bytes(n_kv_heads, max_len) || n < 1 || pos0 < 0 || pos0 + n > max_len) return QUASAR_ERR_SHAPE;
+    if (!aligned(kv_cache, 16) || !aligned(k, 2) || !aligned(v, 2)) return QUASAR_ERR_ALIGN;
+    const long long head_stride = (long long)cache_blocks(max_len) * kKvBlockBytes;
+    unsigned char *kc = static_cast<unsigned char *>(kv_cache), *vc = kc + n_kv_heads * head_stride;
+    const long long ne = (long long)n * n_kv_heads * kHeadDim;
+    const int grid = (int)((ne + 255) / 256 > 4096 ? 4096 : (ne + 255) / 256);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(kv_cache_fill_kernel, dim3(grid), dim3(256), 0, st, k, ne, (int)n_kv_heads, (int)pos0, kc, head_stride, 0);
+    hipLaunchKernelGGL(kv_cache_fill_kernel, dim3(grid), dim3(256), 0, st, v, ne, (int)n_kv_heads, (int)pos0, vc, head_stride, 1);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+int quasar_attn_prepare(const uint16_t *qkv, int64_t M, int64_t ld, int64_t n_q_heads, int64_t n_kv_heads, int64_t L,
+                        const uint16_t *q_gamma, const uint16_t *k_gamma, float eps, float rope_theta, uint16_t *q_out,
+                        int64_t ldq, void *kv_cache, int64_t max_len, void *hip_stream) {
+    if (!qkv || !q_gamma || !k_gamma || !q_out || !kv_cache) return QUASAR_ERR_NULL;
+    AttnShape a{};
+    if (L < 0 || !attn_shape(M, n_q_heads, n_kv_heads, L + M, a)) return QUASAR_ERR_SHAPE;
+    if (!quasar_kv_cache_bytes(n_kv_heads, max_len) || L + M > max_len) return QUASAR_ERR_SHAPE;
+    if (ld < (n_q_heads + 2 * n_kv_heads) * kHeadDim || ldq < n_q_heads * kHeadDim) return QUASAR_ERR_SHAPE;
+    if (!(eps >= 0.f && eps < 1.f) || !(rope_theta > 1.f) || !(rope_theta < 1e30f)) return QUASAR_ERR_SHAPE;
+    if (!aligned(qkv, 2) || !aligned(q_out, 2) || !aligned(kv_cache, 16)) return QUASAR_ERR_ALIGN;
+    const long long head_stride = (long long)cache_blocks(max_len) * kKvBlockBytes;
+    unsigned char *kc = static_cast<unsigned char *>(kv_cache), *vc = kc + n_kv_heads * head_stride;
+    hipLaunchKernelGGL(attn_prepare_kernel, dim3((unsigned int)(M * (n_q_heads + 2 * n_kv_heads))), dim3(64), 0,
+                       static_cast<hipStream_t>(hip_stream), qkv, (long long)ld, (int)M, (int)n_q_heads, (int)n_kv_heads,
+                       (int)L, q_gamma, k_gamma, eps, std::log2((double)rope_theta), q_out, (long long)ldq, kc, vc,
+                       head_stride);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+size_t quasar_attention_workspace_bytes(int64_t M, int64_t n_q_heads, int64_t n_kv_heads, int64_t L_total) {
+    AttnShape a{};
+    if (!attn_shape(M, n_q_heads, n_kv_heads, L_total, a)) return 0;
+    return (size_t)n_kv_heads * a.nsplit * a.NQT * (8 * 64 * 16 + 16 * 2 * 4);
+}
+
+int quasar_verify_attention(const uint16_t *q, int64_t M, int64_t ldq, int64_t n_q_heads, int64_t n_kv_heads,
+                            const void *kv_cache, int64_t max_len, int64_t L_total, uint16_t *out, int64_t ldo,
+                            void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!q || !kv_cache || !out) return QUASAR_ERR_NULL;
+    AttnShape a{};
+    if (!attn_shape(M, n_q_heads, n_kv_heads, L_total, a)) return QUASAR_ERR_SHAPE;
+    if (!quasar_kv_cache_bytes(n_kv_heads, max_len) || L_total > max_len) return QUASAR_ERR_SHAPE;
+    if (ldq < n_q_heads * kHeadDim || ldo < n_q_heads * kHeadDim || ldq % 8 || ldo % 4) return QUASAR_ERR_SHAPE;
+    if (!aligned(q, 16) || !aligned(out, 8) || !aligned(kv_cache, 16)) return QUASAR_ERR_ALIGN;
+    if (!workspace || workspace_bytes < quasar_attention_workspace_bytes(M, n_q_heads, n_kv_heads, L_total))
+        return QUASAR_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return QUASAR_ERR_ALIGN;
+    AttnParams p{};
+    const long long head_stride = (long long)cache_blocks(max_len) * kKvBlockBytes;
+    p.q = q; p.ldq = ldq;
+    p.kcache = static_cast<const unsigned char *>(kv_cache);
+    p.vcache = p.kcache + n_kv_heads * head_stride;
+    p.head_stride = head_stride;
+    p.out = out; p.ldo = ldo;
+    p.part_o = static_cast<float *>(workspace);
+    p.part_ml = p.part_o + (size_t)n_kv_heads * a.nsplit * a.NQT * 8 * 64 * 4;
+    p.M = (int)M; p.G = (int)(n_q_heads / n_kv_heads); p.Hkv = (int)n_kv_heads;
+    p.L_total = (int)L_total; p.nblk = a.nblk; p.nsplit = a.nsplit;
+    p.scale_log2 = 1.4426950408889634f / 11.313708498984761f;      // log2(e) / sqrt(128)
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int lds = kAttnWaves * a.NQT * (8 * 64 * 16 + 16 * 2 * 4);
+    const dim3 grid((unsigned int)a.nsplit, (unsigned int)n_kv_heads);
+    if (a.NQT == 2) {
+        auto kern = verify_attention_kernel<2, kAttnWaves>;
+        if (!allow_large_lds(reinterpret_cast<const void *>(kern))) return QUASAR_ERR_HIP;
+        hipLaunchKernelGGL(kern, grid, dim3(kAttnWaves * 64), lds, st, p);
+    } else {
+        auto kern = verify_attention_kernel<4, kAttnWaves>;
+        if (!allow_large_lds(reinterpret_cast<const void *>(kern))) return QUASAR_ERR_HIP;
+        hipLaunchKernelGGL(kern, grid, dim3(kAttnWaves * 64), lds, st, p);
+    }
+    if (hipGetLastError() != hipSuccess) return QUASAR_ERR_HIP;
+    hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned int)(n_kv_heads * a.NQT)), dim3(512), 0, st, p, a.NQT);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
 /* ---- prompt-lookup n-gram drafter (host side) ---- */
