@@ -494,6 +494,49 @@ def main() -> int:
         detail["fused_blocks_us"] = us_blocks
         detail["fused_block_us_per_layer"] = us_blocks / L
         del fused
+        # the attention of a block: 32 query / 8 key-value heads of 128, M new positions against a cache of
+        # Lc positions; one cache per layer is visited in turn (cold)
+        Hq_, Hkv_ = 32, 8
+        gq = torch.ones(128, dtype=torch.bfloat16, device=dev)
+        for Lc in (4096, 32768):
+            ncache = 36 if Lc <= 4096 else 8
+            caches = []
+            for c in range(ncache):
+                kv = qb.KvCache(Hkv_, Lc + M)
+                gen.manual_seed(synth.seed_for(8, c, Lc % 97))
+                kk = torch.randn((Lc, Hkv_, 128), generator=gen, device=dev).to(torch.bfloat16)
+                vv = torch.randn((Lc, Hkv_, 128), generator=gen, device=dev).to(torch.bfloat16)
+                kv.fill(kk, vv, 0)
+                caches.append(kv)
+                del kk, vv
+            qkv_in = torch.randn((M, (Hq_ + 2 * Hkv_) * 128), generator=gen, device=dev).to(torch.bfloat16)
+            q_buf = torch.empty((M, Hq_ * 128), dtype=torch.bfloat16, device=dev)
+            o_buf = torch.empty((M, Hq_ * 128), dtype=torch.bfloat16, device=dev)
+            wsa = qb.attention_workspace(M, Hq_, Hkv_, Lc + M)
+
+            def attn_pass(prepare, attend):
+                for kv in caches:
+                    if prepare:
+                        qb.attn_prepare(qkv_in, Hq_, kv, Lc, gq, gq, q_out=q_buf)
+                    if attend:
+                        qb.verify_attention(q_buf, Hq_, kv, Lc + M, workspace=wsa, out=o_buf)
+            for label, pr, at_ in (("prepare (norm, rotary, append)", True, False), ("attention", False, True),
+                                   ("prepare + attention", True, True)):
+                attn_pass(True, True)
+                torch.cuda.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(3):
+                    attn_pass(pr, at_)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / (3 * ncache)
+                nb = 2 * (Lc + M) * Hkv_ * 128 * 2
+                extra = f"  {nb / us / 1e3:7.1f} GB/s of cache ({nb / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)" if at_ and not pr else ""
+                log(f"  block attention, cache {Lc:6d} positions, M={M}: {label:32s} {us:7.2f} us{extra}")
+                detail[f"attn_L{Lc}_" + ("prep_" if pr else "") + ("attn_" if at_ else "") + "us"] = us
+            del caches
 
     if args.detail4:
         # 4-bit group-wise weights (0.5 B per weight + 2 B per row and group of 128): the layer shapes cold

@@ -300,24 +300,42 @@ __global__ __launch_bounds__(NW * 64) void verify_attention_kernel(const AttnPar
     }
 }
 
-// Combine the splits: one workgroup of 512 threads per (kv head, query tile); thread = (dt, lane).
+// Combine the splits: one workgroup of 512 threads per (kv head, query tile, 16-d output tile);
+// the 8 waves share the splits (wave g takes splits g, g + 8, ...) and meet twice in LDS: for
+// the maximum over all splits, then for the sums (added in wave order: a fixed order).
 __global__ __launch_bounds__(512) void attention_merge_kernel(const AttnParams p, int NQT) {
-    const int h = blockIdx.x / NQT, qt = blockIdx.x % NQT;
-    const int dt = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __shared__ float smax[8][16];
+    __shared__ float slsum[8][16];
+    __shared__ f32x4 sacc[8][64];
+    const int dt = blockIdx.x & 7, qt = (blockIdx.x >> 3) % NQT, h = (blockIdx.x >> 3) / NQT;
+    const int sg = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int g4 = lane >> 4, col = lane & 15;
     const int r = 16 * qt + col;
-    float mstar = -__builtin_inff();
-    for (int s = 0; s < p.nsplit; ++s)
-        mstar = fmaxf(mstar, p.part_ml[((((long long)h * p.nsplit + s) * NQT + qt) * 16 + col) * 2]);
+    float lmax = -__builtin_inff();
+    for (int s = sg; s < p.nsplit; s += 8)
+        lmax = fmaxf(lmax, p.part_ml[((((long long)h * p.nsplit + s) * NQT + qt) * 16 + col) * 2]);
+    if (g4 == 0) smax[sg][col] = lmax;
+    __syncthreads();
+    float mstar = smax[0][col];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) mstar = fmaxf(mstar, smax[i][col]);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float lsum = 0.f;
-    for (int s = 0; s < p.nsplit; ++s) {
+    for (int s = sg; s < p.nsplit; s += 8) {
         const long long pb = ((long long)h * p.nsplit + s) * NQT + qt;
         const float f = exp2f(p.part_ml[(pb * 16 + col) * 2] - mstar);
         lsum += f * p.part_ml[(pb * 16 + col) * 2 + 1];
         acc += reinterpret_cast<const f32x4 *>(p.part_o)[(pb * 8 + dt) * 64 + lane] * f;
     }
-    if (r >= p.M * p.G) return;
+    sacc[sg][lane] = acc;
+    if (g4 == 0) slsum[sg][col] = lsum;
+    __syncthreads();
+    if (sg != 0 || r >= p.M * p.G) return;
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+        acc += sacc[i][lane];
+        lsum += slsum[i][col];
+    }
     const float inv = __fdiv_rn(1.0f, lsum);
     const int m = r / p.G, g = r % p.G;
     u32x2 o;

@@ -1154,7 +1154,7 @@ bool attn_shape(int64_t M, int64_t Hq, int64_t Hkv, int64_t L_total, AttnShape &
     if (R > 64) return false;
     a.NQT = R <= 32 ? 2 : 4;
     a.nblk = (int)((L_total + kKvBlock - 1) / kKvBlock);
-    int64_t cap = 2 * (int64_t)device_cus() / Hkv;
+    int64_t cap = (int64_t)device_cus() / Hkv;                     // one workgroup per compute unit in total
     if (cap < 1) cap = 1;
     int64_t ns = a.nblk / kAttnWaves;
     if (ns < 1) ns = 1;
@@ -1246,7 +1246,7 @@ int quasar_verify_attention(const uint16_t *q, int64_t M, int64_t ldq, int64_t n
         hipLaunchKernelGGL(kern, grid, dim3(kAttnWaves * 64), lds, st, p);
     }
     if (hipGetLastError() != hipSuccess) return QUASAR_ERR_HIP;
-    hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned int)(n_kv_heads * a.NQT)), dim3(512), 0, st, p, a.NQT);
+    hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned int)(n_kv_heads * a.NQT * 8)), dim3(512), 0, st, p, a.NQT);
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
