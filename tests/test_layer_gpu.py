@@ -165,3 +165,60 @@ def test_fused_argument_errors(qb):
         qb.w8_gateup_swiglu(x, wq, sc, 24)                                   # I not a multiple of 16
     with pytest.raises(qb.QuasarError):
         qb.w8_gateup_swiglu(x, wq, sc, 32, y=torch.zeros((4, 34), dtype=torch.bfloat16, device="cuda")[:, :32])   # ldy % 4
+
+
+def test_whole_decoder_block_against_composed_oracle(qb):
+    """One decoder block of a small Qwen3-shaped model as the library runs it (six launches):
+    RMSNorm -> q/k/v, per-head norm + rotary + cache append, attention over prompt + new positions,
+    o_proj + residual, RMSNorm -> gate/up -> SwiGLU, down_proj + residual - against the same chain
+    composed from the oracles.  The tolerance is the linear bar: one bf16 unit in the last place of
+    an intermediate moves the result by far less."""
+    from oracle import quasar_attention_ref as at
+    say("whole block")
+    M, H, Hq, Hkv, I, L, theta, eps = 8, 1024, 8, 2, 2048, 300, 1.0e6, 1e-6
+    D = 128
+    r = np.random.Generator(np.random.Philox(91))
+    def w_(n, k, seed):
+        return synth.normal_weights(n, k, seed=synth.seed_for(12, 0, seed))
+    def g_(n):
+        return synth.to_bf16_bits((1.0 + 0.1 * r.standard_normal(n)).astype(np.float32))
+    w_qkv, w_o, w_g, w_u, w_d = w_((Hq + 2 * Hkv) * D, H, 1), w_(H, Hq * D, 2), w_(I, H, 3) * np.float32(2), w_(I, H, 4), w_(H, I, 5)
+    g1, g2, gq, gk = g_(H), g_(H), g_(D), g_(D)
+    hid = synth.to_bf16_bits((r.standard_normal((M, H)) * 2).astype(np.float32))
+    kp = synth.to_bf16_bits(r.standard_normal((L, Hkv, D)).astype(np.float32))
+    vp = synth.to_bf16_bits(r.standard_normal((L, Hkv, D)).astype(np.float32))
+
+    # ---- oracle chain
+    q_qkv, s_qkv = ref.quantize_weights(w_qkv)
+    q_o, s_o = ref.quantize_weights(w_o)
+    q_g, s_g = ref.quantize_weights(w_g)
+    q_u, s_u = ref.quantize_weights(w_u)
+    q_d, s_d = ref.quantize_weights(w_d)
+    qkv = lr.fused_linear(hid, q_qkv, s_qkv, gamma_bits=g1, eps=eps).reshape(M, Hq + 2 * Hkv, D)
+    pos = np.arange(L, L + M)
+    qh = at.head_norm_rope(qkv[:, :Hq], gq, eps, pos, theta)
+    kh = at.head_norm_rope(qkv[:, Hq:Hq + Hkv], gk, eps, pos, theta)
+    att = at.verify_attention(qh, np.concatenate([kp, kh]), np.concatenate([vp, qkv[:, Hq + Hkv:]])).reshape(M, Hq * D)
+    h1 = lr.fused_linear(att, q_o, s_o, residual_bits=hid)
+    act = lr.gateup_swiglu(h1, q_g, s_g, q_u, s_u, gamma_bits=g2, eps=eps)
+    want = lr.fused_linear(act, q_d, s_d, residual_bits=h1)
+
+    # ---- the library
+    wq_qkv, sc_qkv = qb.quantize_weights(f32_to_dev(w_qkv))
+    wq_o, sc_o = qb.quantize_weights(f32_to_dev(w_o))
+    wq_gu, sc_gu = qb.quantize_weights(qb.interleave_gate_up(f32_to_dev(w_g), f32_to_dev(w_u)))
+    wq_d, sc_d = qb.quantize_weights(f32_to_dev(w_d))
+    cache = qb.KvCache(Hkv, L + M)
+    cache.buf.fill_(0xFF)
+    cache.fill(bf16_to_dev(kp), bf16_to_dev(vp), 0)
+    h = bf16_to_dev(hid).clone()
+    qkv_d = qb.w8_linear_fused(h, wq_qkv, sc_qkv, (Hq + 2 * Hkv) * D, gamma=bf16_to_dev(g1), eps=eps)
+    q_d_ = qb.attn_prepare(qkv_d, Hq, cache, L, bf16_to_dev(gq), bf16_to_dev(gk), eps=eps, rope_theta=theta)
+    att_d = qb.verify_attention(q_d_, Hq, cache, L + M)
+    qb.w8_linear_fused(att_d, wq_o, sc_o, H, residual=h, y=h)
+    act_d = qb.w8_gateup_swiglu(h, wq_gu, sc_gu, I, gamma=bf16_to_dev(g2), eps=eps)
+    qb.w8_linear_fused(act_d, wq_d, sc_d, H, residual=h, y=h)
+    torch.cuda.synchronize()
+    e = err(h, want)
+    say("   block rel err", e)
+    assert e <= TOL
