@@ -536,6 +536,69 @@ def main() -> int:
                 extra = f"  {nb / us / 1e3:7.1f} GB/s of cache ({nb / us / 1e3 / HBM_PEAK_GBPS:.1%} of peak)" if at_ and not pr else ""
                 log(f"  block attention, cache {Lc:6d} positions, M={M}: {label:32s} {us:7.2f} us{extra}")
                 detail[f"attn_L{Lc}_" + ("prep_" if pr else "") + ("attn_" if at_ else "") + "us"] = us
+            if Lc == 4096:
+                # A COMPLETE verification step of the Qwen3-8B-shaped model, every operation included, as separate
+                # launches: per block norm->q/k/v, prepare, attention (2 launches), o+residual, norm->gate/up->SwiGLU,
+                # down+residual; then the vocabulary verify.  Eager, and replayed from a captured graph (no launch
+                # gaps from the host).  Context 4096 positions, M new ones.
+                fused2 = []
+                for lin in layers:
+                    d = {name: (wq, sc) for name, K, N, wq, sc, wp in lin}
+                    tg = I // 16
+                    fused2.append((torch.cat([d["q_proj"][0], d["k_proj"][0], d["v_proj"][0]]),
+                                   torch.cat([d["q_proj"][1], d["k_proj"][1], d["v_proj"][1]]),
+                                   d["o_proj"][0], d["o_proj"][1],
+                                   torch.stack([d["gate_proj"][0].view(tg, -1), d["up_proj"][0].view(tg, -1)], dim=1).reshape(-1),
+                                   torch.stack([d["gate_proj"][1].view(tg, 16), d["up_proj"][1].view(tg, 16)], dim=1).reshape(-1),
+                                   d["down_proj"][0], d["down_proj"][1]))
+
+                def full_step():
+                    hid.copy_(h0)
+                    for (wqkv, sqkv, wo, so, wgu, sgu, wd, sd), kv in zip(fused2, caches):
+                        qb.w8_linear_fused(hid, wqkv, sqkv, 6144, gamma=gam, eps=1e-6, y=qkv)
+                        qb.attn_prepare(qkv, Hq_, kv, Lc, gq, gq, q_out=q_buf)
+                        qb.verify_attention(q_buf, Hq_, kv, Lc + M, workspace=wsa, out=o_buf)
+                        qb.w8_linear_fused(o_buf, wo, so, H, residual=hid, y=hid)
+                        qb.w8_gateup_swiglu(hid, wgu, sgu, I, gamma=gam, eps=1e-6, y=act)
+                        qb.w8_linear_fused(act, wd, sd, H, residual=hid, y=hid)
+                    qb.lmhead_verify(hid, head_q, head_s, V, draft, ws, out_argmax, out_accept)
+                full_step()
+                torch.cuda.synchronize()
+                assert torch.isfinite(hid.float()).all()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(3):
+                    full_step()
+                e1.record()
+                torch.cuda.synchronize()
+                us_eager = e0.elapsed_time(e1) * 1e3 / 3
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    full_step()
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph, stream=side):
+                        full_step()
+                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.synchronize()
+                ref_am = out_argmax.clone()
+                graph.replay()
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(5):
+                    graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                us_graph = e0.elapsed_time(e1) * 1e3 / 5
+                assert torch.equal(out_argmax, ref_am), "graph replay differs from the eager step"
+                nlaunch = 7 * L + 2
+                log(f"  COMPLETE step (36 blocks with attention over {Lc} cached positions + vocabulary verify), {nlaunch} launches: "
+                    f"eager {us_eager:.1f} us, captured graph {us_graph:.1f} us "
+                    f"({weight_bytes / us_graph / 1e3:.1f} GB/s of int8 weights)")
+                detail["complete_step_eager_us"] = us_eager
+                detail["complete_step_graph_us"] = us_graph
+                del graph, fused2
             del caches
 
     if args.detail4:
