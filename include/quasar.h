@@ -398,11 +398,12 @@ int quasar_w8_gateup_swiglu(const uint16_t *x, int64_t M, int64_t K, int64_t ldx
  *
  * quasar_verify_attention: out[m, h, :] = softmax_j( q[m, h, :] . k[j, h / G, :] / sqrt(128) ) v[j, h / G, :]
  *   over the cached positions j <= L_total - M + m (the M queries are the last M cached positions,
- *   causal among themselves), G = n_q_heads / n_kv_heads, M * G <= 64; probabilities enter the
+ *   causal among themselves), G = n_q_heads / n_kv_heads (64 query rows m * G + g per pass over the
+ *   cache; more rows take more passes); probabilities enter the
  *   second product as bf16, sums are fp32, one rounding of the output to bf16.  q as written by
  *   quasar_attn_prepare (16-byte aligned, ldq a multiple of 8); out [M, n_q_heads * 128] bf16, row
  *   stride ldo a multiple of 4; workspace: quasar_attention_workspace_bytes(M, n_q_heads, n_kv_heads, L_total)
- *   bytes (partial results of the splits over the positions).  Two launches.
+ *   bytes (partial results of the splits over the positions).  Two launches per pass.
  */
 size_t quasar_kv_cache_bytes(int64_t n_kv_heads, int64_t max_len);   /* 0 on invalid arguments */
 int quasar_kv_cache_fill(const uint16_t *k, const uint16_t *v, int64_t n, int64_t n_kv_heads, int64_t pos0,

@@ -37,6 +37,7 @@ struct AttnParams {
     float *part_o;            // [Hkv][nsplit][NQT][8][64] f32x4
     float *part_ml;           // [Hkv][nsplit][NQT][16][2]
     int M, G, Hkv, L_total, nblk, nsplit;
+    int row0;                 // first query row (m * G + g) of this launch; rows row0 .. row0 + 16 NQT - 1
     float scale_log2;         // log2(e) / sqrt(128)
 };
 
@@ -114,7 +115,8 @@ __global__ __launch_bounds__(256) void kv_cache_fill_kernel(const uint16_t *src,
 }
 
 // ---------------------------------------------------------------------------------------------
-// Main kernel.  NQT = number of 16-row query tiles (rows r = m * G + g, r < M * G <= 16 NQT).
+// Main kernel.  NQT = number of 16-row query tiles of one launch (rows r = m * G + g, starting at
+// row0; rows at or beyond M * G are padding).  More than 64 rows take several launches.
 // ---------------------------------------------------------------------------------------------
 template <int NQT, int NW>
 __global__ __launch_bounds__(NW * 64) void verify_attention_kernel(const AttnParams p) {
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(NW * 64) void verify_attention_kernel(const AttnPar
     int limit[NQT];                       // last visible position of this lane's query column
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
-        const int r = 16 * qt + col;
+        const int r = p.row0 + 16 * qt + col;
         const int m = r < R ? r / p.G : p.M - 1, g = r < R ? r % p.G : 0;
         limit[qt] = p.L_total - p.M + m;
 #pragma unroll
@@ -310,7 +312,7 @@ __global__ __launch_bounds__(512) void attention_merge_kernel(const AttnParams p
     const int dt = blockIdx.x & 7, qt = (blockIdx.x >> 3) % NQT, h = (blockIdx.x >> 3) / NQT;
     const int sg = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int g4 = lane >> 4, col = lane & 15;
-    const int r = 16 * qt + col;
+    const int r = p.row0 + 16 * qt + col;
     float lmax = -__builtin_inff();
     for (int s = sg; s < p.nsplit; s += 8)
         lmax = fmaxf(lmax, p.part_ml[((((long long)h * p.nsplit + s) * NQT + qt) * 16 + col) * 2]);

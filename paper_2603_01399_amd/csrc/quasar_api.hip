@@ -1151,8 +1151,8 @@ bool attn_shape(int64_t M, int64_t Hq, int64_t Hkv, int64_t L_total, AttnShape &
     if (M < 1 || M > 32 || Hkv < 1 || Hkv > 1024 || Hq < Hkv || Hq % Hkv || Hq > 4096) return false;
     if (L_total < M || L_total > (1 << 24)) return false;
     const int64_t R = M * (Hq / Hkv);
-    if (R > 64) return false;
-    a.NQT = R <= 32 ? 2 : 4;
+    if (R > 1024) return false;
+    a.NQT = R <= 32 ? 2 : 4;                                       // rows per launch: 32 or 64
     a.nblk = (int)((L_total + kKvBlock - 1) / kKvBlock);
     int64_t cap = (int64_t)device_cus() / Hkv;                     // one workgroup per compute unit in total
     if (cap < 1) cap = 1;
@@ -1236,18 +1236,23 @@ int quasar_verify_attention(const uint16_t *q, int64_t M, int64_t ldq, int64_t n
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int lds = kAttnWaves * a.NQT * (8 * 64 * 16 + 16 * 2 * 4);
     const dim3 grid((unsigned int)a.nsplit, (unsigned int)n_kv_heads);
-    if (a.NQT == 2) {
-        auto kern = verify_attention_kernel<2, kAttnWaves>;
-        if (!allow_large_lds(reinterpret_cast<const void *>(kern))) return QUASAR_ERR_HIP;
-        hipLaunchKernelGGL(kern, grid, dim3(kAttnWaves * 64), lds, st, p);
-    } else {
-        auto kern = verify_attention_kernel<4, kAttnWaves>;
-        if (!allow_large_lds(reinterpret_cast<const void *>(kern))) return QUASAR_ERR_HIP;
-        hipLaunchKernelGGL(kern, grid, dim3(kAttnWaves * 64), lds, st, p);
+    const int R = (int)(M * (n_q_heads / n_kv_heads));
+    for (int row0 = 0; row0 < R; row0 += 16 * a.NQT) {             // 64 query rows per pass over the cache
+        p.row0 = row0;
+        if (a.NQT == 2) {
+            auto kern = verify_attention_kernel<2, kAttnWaves>;
+            if (!allow_large_lds(reinterpret_cast<const void *>(kern))) return QUASAR_ERR_HIP;
+            hipLaunchKernelGGL(kern, grid, dim3(kAttnWaves * 64), lds, st, p);
+        } else {
+            auto kern = verify_attention_kernel<4, kAttnWaves>;
+            if (!allow_large_lds(reinterpret_cast<const void *>(kern))) return QUASAR_ERR_HIP;
+            hipLaunchKernelGGL(kern, grid, dim3(kAttnWaves * 64), lds, st, p);
+        }
+        if (hipGetLastError() != hipSuccess) return QUASAR_ERR_HIP;
+        hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned int)(n_kv_heads * a.NQT * 8)), dim3(512), 0, st, p, a.NQT);
+        if (hipGetLastError() != hipSuccess) return QUASAR_ERR_HIP;
     }
-    if (hipGetLastError() != hipSuccess) return QUASAR_ERR_HIP;
-    hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned int)(n_kv_heads * a.NQT * 8)), dim3(512), 0, st, p, a.NQT);
-    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+    return QUASAR_OK;
 }
 
 /* ---- prompt-lookup n-gram drafter (host side) ---- */

@@ -91,7 +91,8 @@ def test_cache_roundtrip_through_one_visible_key(qb):
 
 
 ATT = [(8, 32, 8, 40), (8, 32, 8, 4096), (8, 32, 8, 4099), (1, 32, 8, 1000), (5, 8, 2, 33), (16, 16, 4, 700),
-       (8, 4, 4, 257), (3, 40, 8, 129), (8, 32, 8, 20000), (16, 32, 8, 3000), (8, 8, 1, 96)]
+       (8, 4, 4, 257), (3, 40, 8, 129), (8, 32, 8, 20000), (16, 32, 8, 3000), (8, 8, 1, 96),
+       (32, 32, 8, 600), (20, 16, 2, 321)]                       # more than 64 query rows per kv head: several passes
 
 
 @pytest.mark.parametrize("M,Hq,Hkv,Lt", ATT)
@@ -168,6 +169,6 @@ def test_attention_argument_errors(qb):
         qb.verify_attention(q, 30, cache, 32)                                # heads not a multiple
     with pytest.raises(qb.QuasarError):
         qb.verify_attention(q, 32, cache, 32, workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
-    big = torch.zeros((32, 32 * 128), dtype=torch.bfloat16, device="cuda")
+    big = torch.zeros((33, 32 * 128), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(qb.QuasarError):
-        qb.verify_attention(big, 32, cache, 64)                              # M * G > 64
+        qb.verify_attention(big, 32, cache, 64)                              # M > 32
