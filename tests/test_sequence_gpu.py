@@ -192,6 +192,45 @@ def test_sequence_rerun_with_new_input_sees_fresh_activations(qb):
                 assert ref.rel_maxabs_err(got, want[li][name][0]) <= TOL, (li, name)
 
 
+def test_sequence_replayed_from_a_captured_graph(qb):
+    """The whole-step launch captured into a HIP graph (its two kernels, no memset node) and
+    replayed several times, with eager work and new inputs between the replays: every replay must
+    give the bits of the eager run on the same input."""
+    print("sequence graph replay", flush=True)
+    M, hidden, kv, inter, n_layers = 8, 256, 64, 768, 2
+    layers = build_model(qb, n_layers, hidden, kv, inter, seed=9850)
+    inputs = [synth.activations_bf16(M, hidden, seed=9851 + i) for i in range(3)]
+    bufs, h_dev = gpu_buffers(layers, M, inputs[0])
+    seq = qb.Sequence(linear_list(layers, bufs))
+    eager = []
+    for xb in inputs:
+        bufs[0]["in"].copy_(bf16_to_dev(xb))
+        seq.run()
+        torch.cuda.synchronize()
+        eager.append([bf16_to_host(bufs[li]["down"]) for li in range(n_layers)])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        seq.run()                                            # warm-up on the capture stream
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            seq.run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for rep in range(6):
+        i = rep % 3
+        bufs[0]["in"].copy_(bf16_to_dev(inputs[i]))
+        scratch.add_(1.0)                                    # unrelated eager work between the replays
+        for li in range(n_layers):
+            bufs[li]["down"].zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert not seq.timed_out()
+        for li in range(n_layers):
+            assert np.array_equal(bf16_to_host(bufs[li]["down"]), eager[i][li]), (rep, li)
+
+
 def test_sequence_reused_buffers_fall_back_to_barriers(qb):
     """Ping-pong activation buffers (written more than once per step) must be ordered by
     device-wide barriers; results stay identical to the single-call path."""
