@@ -86,3 +86,26 @@ def test_argument_validation_without_launch(qb):
     assert qz(a, 0, 1024, 1024, 512, a, a, None) == ERR_SHAPE
     assert L.quasar_read_stream(a, 1000, a, None) == ERR_SHAPE
     assert L.quasar_copy_stream(a, None, 1024, None) == ERR_NULL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more exits with a message instead of running."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0 and "one GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_sizes_of_the_newer_formats(qb):
+    lib = qb.lib()
+    # 4-bit: half a byte per weight + one bf16 step size per row and group of 128
+    assert lib.quasar_w4_packed_bytes(4096, 4096) == 4096 * 4096 // 2 + 2 * 4096 * 32
+    assert lib.quasar_w4_packed_bytes(4096, 4096 + 64) == 0 and lib.quasar_w4_packed_bytes(24, 128) == 0
+    # key/value cache: keys and values, blocks of 32 positions x 128 x bf16 per kv head
+    assert lib.quasar_kv_cache_bytes(8, 4096) == 2 * 8 * 128 * 8192
+    assert lib.quasar_kv_cache_bytes(8, 4097) == 2 * 8 * 129 * 8192 and lib.quasar_kv_cache_bytes(8, 0) == 0
+    # attention workspace: positive for valid shapes, 0 otherwise
+    assert lib.quasar_attention_workspace_bytes(8, 32, 8, 4104) > 0
+    assert lib.quasar_attention_workspace_bytes(8, 30, 8, 4104) == 0 and lib.quasar_attention_workspace_bytes(8, 32, 8, 4) == 0
+    assert lib.quasar_sample_workspace_bytes(8, 151936) >= 8 * 151936 * 4
