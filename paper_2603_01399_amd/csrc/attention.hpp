@@ -168,13 +168,16 @@ __global__ __launch_bounds__(NW * 64) void verify_attention_kernel(const AttnPar
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { mrow[qt] = -__builtin_inff(); lrow[qt] = 0.f; }
 
+    // One block of prefetch.  The loads are issued unconditionally (the last iteration fetches its
+    // own block once more, a cache hit) so that the compiler can count them: with a conditional
+    // prefetch it has to assume the shorter queue and waits for the prefetched block before the
+    // current one is used.
     u32x4 kc[8], vc[8];
     int b = b0 + w;
-    if (b < b1) load_block(b, kc, vc);
+    load_block(min(b, b1 - 1), kc, vc);
     for (; b < b1; b += NW) {
         u32x4 kn[8], vn[8];
-        const bool more = b + NW < b1;
-        if (more) load_block(b + NW, kn, vn);
+        load_block(min(b + NW, b1 - 1), kn, vn);
 
         const int pos0 = b * kKvBlock;
         const bool edge = pos0 + kKvBlock - 1 > p.L_total - p.M;      // some position may be hidden from some query
@@ -205,7 +208,6 @@ __global__ __launch_bounds__(NW * 64) void verify_attention_kernel(const AttnPar
                 for (int ks = 0; ks < 4; ++ks)
                     s[sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[sub * 4 + ks]), qb[qt][ks],
                                                                      s[sub], 0, 0, 0);
-                s[sub] *= p.scale_log2;
             }
             if (edge) {
 #pragma unroll
@@ -217,51 +219,58 @@ __global__ __launch_bounds__(NW * 64) void verify_attention_kernel(const AttnPar
                     if (pb + 3 > limit[qt]) s[sub].w = -__builtin_inff();
                 }
             }
+            // running maximum in units of the raw scores; exponentials as exp2(raw * c - max * c) in one
+            // fused multiply-add each (c = log2(e) / sqrt(128) > 0 keeps the order)
             float mx = fmaxf(fmaxf(fmaxf(s[0].x, s[0].y), fmaxf(s[0].z, s[0].w)),
                              fmaxf(fmaxf(s[1].x, s[1].y), fmaxf(s[1].z, s[1].w)));
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(mrow[qt], mx);
             const float m_use = m_new == -__builtin_inff() ? 0.f : m_new;     // nothing visible yet
-            const float alpha = exp2f(mrow[qt] - m_use);                      // 0 while mrow is -inf
+            const float mc = -m_use * p.scale_log2;
+            const float alpha = __builtin_amdgcn_exp2f(__builtin_fmaf(mrow[qt], p.scale_log2, mc));   // 0 while mrow is -inf
             mrow[qt] = m_new;
             float pr[8];
-            pr[0] = exp2f(s[0].x - m_use); pr[1] = exp2f(s[0].y - m_use);
-            pr[2] = exp2f(s[0].z - m_use); pr[3] = exp2f(s[0].w - m_use);
-            pr[4] = exp2f(s[1].x - m_use); pr[5] = exp2f(s[1].y - m_use);
-            pr[6] = exp2f(s[1].z - m_use); pr[7] = exp2f(s[1].w - m_use);
-            // the probabilities enter the second product as bf16; the row sum uses the same rounded
-            // values so that the weights that are applied sum to one
-            u32x4 pb16;
-            unsigned int pw[8];
+            pr[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[0].x, p.scale_log2, mc));
+            pr[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[0].y, p.scale_log2, mc));
+            pr[2] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[0].z, p.scale_log2, mc));
+            pr[3] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[0].w, p.scale_log2, mc));
+            pr[4] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[1].x, p.scale_log2, mc));
+            pr[5] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[1].y, p.scale_log2, mc));
+            pr[6] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[1].z, p.scale_log2, mc));
+            pr[7] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[1].w, p.scale_log2, mc));
+            // the probabilities enter the second product as bf16 (hardware conversion, nearest even);
+            // the row sum uses the same rounded values so that the weights that are applied sum to one
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            unsigned int pk[4];
             float psum = 0.f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                pw[i] = float_to_bf16_bits(pr[i]);
-                psum += bf16_bits_to_float(pw[i]);
+            for (int i = 0; i < 4; ++i) {
+                const bf16x2 h2 = __builtin_convertvector(f32x2{pr[2 * i], pr[2 * i + 1]}, bf16x2);
+                pk[i] = __builtin_bit_cast(unsigned int, h2);
+                psum += __uint_as_float(pk[i] << 16) + __uint_as_float(pk[i] & 0xFFFF0000u);
             }
-            pb16.x = pw[0] | (pw[1] << 16);
-            pb16.y = pw[2] | (pw[3] << 16);
-            pb16.z = pw[4] | (pw[5] << 16);
-            pb16.w = pw[6] | (pw[7] << 16);
+            const u32x4 pb16 = {pk[0], pk[1], pk[2], pk[3]};
             lrow[qt] = lrow[qt] * alpha + psum;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ull) {        // some row's maximum moved
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                oacc[dt][qt] *= alpha;
+                for (int dt = 0; dt < 8; ++dt) oacc[dt][qt] *= alpha;
+            }
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
                 oacc[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vc[dt]),
                                                                        __builtin_bit_cast(bf16x8, pb16), oacc[dt][qt], 0, 0, 0);
-            }
         }
-        if (more) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) { kc[i] = kn[i]; vc[i] = vn[i]; }
-        }
+        for (int i = 0; i < 8; ++i) { kc[i] = kn[i]; vc[i] = vn[i]; }
     }
-    // the four lanes of a query column hold partial row sums
+    // the four lanes of a query column hold partial row sums; the maxima go on in log2 units
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
         lrow[qt] += __shfl_xor(lrow[qt], 16, 64);
         lrow[qt] += __shfl_xor(lrow[qt], 32, 64);
+        mrow[qt] *= p.scale_log2;
     }
 
     // ---- merge the waves through LDS: [NW][NQT][8][64] f32x4 outputs, [NW][NQT][16][2] (max, sum)
