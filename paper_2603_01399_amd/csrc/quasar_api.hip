@@ -821,6 +821,7 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
 
     int xs_max = 0, sc_max = 0, acc_max = 0;
     for (SeqPhase &p : phases) {
+        if ((long long)p.T * (G + 1) >= (1ll << 31)) return QUASAR_ERR_SHAPE;   // the kernel splits tiles in 32 bits
         int xs, sc, ac;
         plan_phase(p, MP, w16, a8, G, xs, sc, ac);
         if (xs > xs_max) xs_max = xs;

@@ -149,6 +149,10 @@ __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int ta
 #ifndef QUASAR_SEQ_XB
 #define QUASAR_SEQ_XB 8
 #endif
+// Ring slots are refilled in groups of this many, after the group's last slot has been used.
+#ifndef QUASAR_SEQ_GR
+#define QUASAR_SEQ_GR 4
+#endif
 
 // A8 selects the W8A8 form of the linears: the activations are smoothed and quantised per
 // token while they are staged (same arithmetic as stream_w8a8.hpp), the weight step goes
@@ -162,6 +166,8 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
     constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
     constexpr int XB = QUASAR_SEQ_XB;
+    constexpr int GR = QUASAR_SEQ_GR;
+    static_assert(GR >= 1 && (GR & (GR - 1)) == 0 && D % GR == 0, "refill groups tile the ring");
     constexpr int nthreads = NW * 64;
     static_assert(NW == 16, "the in-kernel second stage of the verify phase assumes 1024 threads");
 
@@ -225,8 +231,8 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             if (l_ph < nph && l_c >= phases[l_ph].C) { ++l_ph; l_c = 0; }
             if (l_ph >= nph) { l_ntiles = 0; l_spw = 0; return; }
             const auto &P = phases[l_ph];
-            l_t0 = (int)(((long long)P.T * b) / G);
-            l_ntiles = (int)(((long long)P.T * (b + 1)) / G) - l_t0;
+            l_t0 = (int)(((unsigned int)P.T * (unsigned int)b) / (unsigned int)G);   // the host checks T * G < 2^31
+            l_ntiles = (int)(((unsigned int)P.T * (unsigned int)(b + 1)) / (unsigned int)G) - l_t0;
             if (l_ntiles == 0) { l_c = P.C - 1; continue; }
             const int scc = min(P.SC, P.S - l_c * P.SC);
             l_s_lo = (scc * w) / NW;
@@ -557,8 +563,8 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 QUASAR_TRACE(0)
                 c_C = P.C;
                 c_kind = P.kind;
-                c_t0 = (int)(((long long)P.T * b) / G);
-                c_ntiles = (int)(((long long)P.T * (b + 1)) / G) - c_t0;
+                c_t0 = (int)(((unsigned int)P.T * (unsigned int)b) / (unsigned int)G);
+                c_ntiles = (int)(((unsigned int)P.T * (unsigned int)(b + 1)) / (unsigned int)G) - c_t0;
                 if (P.wait == SEQ_WAIT_BARRIER) {
                     ++barriers_done;
                     grid_barrier(sp.sync, barriers_done * (unsigned int)G, sp.spin_limit);
@@ -620,14 +626,14 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             QUASAR_TRACE_SLOT(1)
             const u32x4 wv = ring[d];
             const unsigned char *xp = xsb + (xlane + c_xoff);
-            const unsigned long long la = l_base;
+            [[maybe_unused]] const unsigned long long la = l_base;
             bf16x8 a0, a1;
             if constexpr (A8) {
-                ring[d] = ring_refill_at(la, voff, wv);
+                if constexpr (GR == 1) ring[d] = ring_refill_at(la, voff, wv);
             } else if constexpr (!W16) {
                 a0 = codes_to_bf16x8(wv.x, wv.y);
                 a1 = codes_to_bf16x8(wv.z, wv.w);
-                ring[d] = ring_refill_at(la, voff, wv);
+                if constexpr (GR == 1) ring[d] = ring_refill_at(la, voff, wv);
             } else {
                 a0 = __builtin_bit_cast(bf16x8, wv);
             }
@@ -648,9 +654,11 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     }
                 }
             }
-            if constexpr (W16) ring[d] = ring_refill_at(la, voff, wv);
-            l_base += l_inc;
-            if (__builtin_expect(--l_left == 0, 0)) l_event();
+            if constexpr (GR == 1) {
+                if constexpr (W16) ring[d] = ring_refill_at(la, voff, wv);
+                l_base += l_inc;
+                if (__builtin_expect(--l_left == 0, 0)) l_event();
+            }
             QUASAR_TRACE_SLOT(4)
             if (!nocomp && __builtin_expect(--c_left == 0, 0)) {
                 // ---- tile end: cross-wave sum through LDS, fixed order (W8A8: exact integers)
@@ -666,7 +674,9 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                         acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
                     }
                 }
+                QUASAR_TRACE_SLOT(6)
                 lds_barrier();
+                QUASAR_TRACE_SLOT(7)
                 // the epilogue rotates over waves 1..NW-1: wave 0 polls for the next phase's input
                 // and should never have to wait for its own stores
                 if (w == 1 + (c_tl % (NW - 1))) {
@@ -683,6 +693,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                             if (c_c < c_C - 1) *a = rsum[nb];
                         }
                     }
+                    QUASAR_TRACE_SLOT(8)
                     if (c_c == c_C - 1) {
                         const int n0 = (c_t0 + c_tl - c_tb) * kTileRows + 4 * g;
                         float s4[4] = {1.f, 1.f, 1.f, 1.f};
@@ -738,6 +749,20 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     if (__builtin_expect(c_t0 + c_tl == c_seg_end, 0)) c_reseg();
                     c_left = c_nsl;
                     c_xoff = c_x0;
+                }
+            }
+            // ---- the group's refills, in slot order, once its last slot (and a tile end that fell
+            // on it) is done: a load issued while the compute unit's memory pipeline is full blocks
+            // the wave at the instruction, so after a wait - ring full, pipeline empty - the landed
+            // slots are all used, and a tile's partial sums handed over, before the first refill
+            if constexpr (GR > 1) {
+                if ((d & (GR - 1)) == GR - 1) {
+#pragma unroll
+                    for (int e = d - (GR - 1); e <= d; ++e) {
+                        ring[e] = ring_refill_at(l_base, voff, ring[e]);
+                        l_base += l_inc;
+                        if (__builtin_expect(--l_left == 0, 0)) l_event();
+                    }
                 }
             }
         }
