@@ -14,9 +14,9 @@
 // Each wave walks ONE flat sequence of slots over the whole step:
 //     for phase, for K chunk, for tile of this workgroup, for step of this wave's K slice
 // (at least one slot per tile so that all waves meet at every tile end; the slots of one
-// (phase, chunk) are padded with slots of zeros to a multiple of D).  Slot j is loaded into
-// ring[j % D] D slots before it is consumed, so the ring holds the weights of the following
-// phases while the workgroup waits for activations.
+// (phase, chunk) are padded with slots of zeros to a multiple of the refill group, 4).  Slot j
+// is loaded into ring[j % D] D - 3 .. D slots before it is consumed, so the ring holds the
+// weights of the following phases while the workgroup waits for activations.
 #pragma once
 
 #include "stream_w8a8.hpp"
@@ -247,14 +247,14 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
         else { l_base = zeros; l_inc = 0u; l_left = l_ph < nph ? 1 : kForever; }
     };
     // a wave's slots of one (phase, chunk) - a "unit" - are padded with slots of zeros to a
-    // multiple of D, so that every unit starts at ring[0]
+    // multiple of GR, so that every unit starts at the first slot of a refill group
     bool l_in_pad = false;
     auto l_event = [&]() {
         if (l_ph < nph) {
             if (!l_in_pad && ++l_tl < l_ntiles) {
                 if (l_t0 + l_tl == l_seg_end) l_retile(); else l_wt += l_stride;
             } else {
-                const int pad = l_in_pad ? 0 : (-(l_ntiles * max(l_spw, 1))) & (D - 1);
+                const int pad = l_in_pad ? 0 : (-(l_ntiles * max(l_spw, 1))) & (GR - 1);
                 if (pad > 0) {
                     l_in_pad = true;
                     l_base = zeros;
@@ -592,7 +592,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             c_tl = 0;
             c_left = c_nsl;
             c_xoff = c_x0;
-            unit_left = (c_ntiles * c_nsl + D - 1) & ~(D - 1);
+            unit_left = (c_ntiles * c_nsl + GR - 1) & ~(GR - 1);
             nocomp = false;
             c_reseg();
             QUASAR_TRACE(1)
@@ -607,22 +607,34 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             return true;
         }
     };
-    // Units start at a round boundary, so the entry code exists once, in front of the round.
-    // The end of a run and the end of a tile can fall on any slot and are inlined into every
-    // slot of the unrolled round (the build raises the compiler's pragma-unroll size limit for
+    // Units start at a group boundary (every GR slots), so the entry code exists D / GR times in the
+    // unrolled round.  The end of a run and the end of a tile can fall on any slot and are inlined
+    // into every slot of the round (the build raises the compiler's pragma-unroll size limit for
     // this): any other shape - a side exit from the round, or re-entering it through a switch -
-    // makes the compiler lose count of the outstanding ring loads and drain the ring.
+    // makes the compiler lose count of the outstanding ring loads and drain the ring.  When the
+    // sequence ends in the middle of a round the rest of the round runs without arithmetic and the
+    // loop is left at its top.
 #ifdef QUASAR_SEQ_TRACE
     int trace_n = 0;
 #endif
     const unsigned char *xsb = lds;
+    bool done = false;
     c_leave();
     for (;;) {
-        // ---- round boundary: units begin and end here
-        if (unit_left == 0 && !c_enter()) break;
-        unit_left -= D;
+        if (done) break;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
+            // ---- group boundary: units begin and end here
+            if ((d & (GR - 1)) == 0) {
+                if (unit_left == 0 && !c_enter()) {
+                    // the sequence is over: the rest of the round runs without arithmetic, the loop is left at its top
+                    done = true;
+                    nocomp = true;
+                    unit_left = kForever & ~(GR - 1);
+                }
+                if (d == 0 && done) break;
+                unit_left -= GR;
+            }
             QUASAR_TRACE_SLOT(1)
             const u32x4 wv = ring[d];
             const unsigned char *xp = xsb + (xlane + c_xoff);
