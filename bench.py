@@ -703,7 +703,7 @@ def main() -> int:
         log(f"cpu oracle: {cpu_us / 1e6:.1f} s per step extrapolated ({threads} BLAS threads)")
 
     out = {
-        "metric": "us per verification step (int8 weights, M=8 tokens) + achieved HBM GB/s",
+        "metric": "\u00b5s per verification step + achieved HBM GB/s (int8 weights, M=8 tokens)",
         "value": us_step,
         "unit": "us/step",
         "n_gpus": 1,
