@@ -77,4 +77,13 @@ __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v,
     return ((unsigned long long)hi << 32) | lo;
 }
 
+// floor(T * b / G) for wave-uniform non-negative operands: where a workgroup's share of T tiles
+// begins.  The 64-bit division is a long software routine; it runs only when the product does
+// not fit 32 bits.
+__device__ __forceinline__ int tile_split(int T, int b, int G) {
+    const unsigned long long prod = (unsigned long long)(unsigned int)T * (unsigned int)b;
+    if (prod <= 0xFFFFFFFFull) return (int)((unsigned int)prod / (unsigned int)G);
+    return (int)(prod / (unsigned long long)(unsigned int)G);
+}
+
 }  // namespace quasar

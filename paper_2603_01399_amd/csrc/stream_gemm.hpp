@@ -200,8 +200,8 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
     const int g = lane >> 4, mcol = lane & 15;
 
     constexpr int TU = EPI == EPI_SWIGLU ? 2 : 1;   // tiles are handed out in units of TU
-    const int t0 = TU * (int)(((long long)(p.T / TU) * b) / G);
-    const int t1 = TU * (int)(((long long)(p.T / TU) * (b + 1)) / G);
+    const int t0 = TU * tile_split(p.T / TU, b, G);
+    const int t1 = TU * tile_split(p.T / TU, b + 1, G);
     const int ntiles = t1 - t0;
 
     u32x4 *xs = reinterpret_cast<u32x4 *>(lds);                                   // [SC*PPS][MP]
@@ -549,8 +549,8 @@ __global__ __launch_bounds__(NW * 64) void stream_valu_kernel(const GemmParams p
     const int g = lane >> 4, i16 = lane & 15;
 
     const int G = gridDim.x, b = blockIdx.x;
-    const int t0 = (int)(((long long)p.T * b) / G);
-    const int t1 = (int)(((long long)p.T * (b + 1)) / G);
+    const int t0 = tile_split(p.T, b, G);
+    const int t1 = tile_split(p.T, b + 1, G);
     const int ntiles = t1 - t0;
     const int kc_max = p.SC * kStepK8;
 

@@ -114,8 +114,8 @@ __global__ __launch_bounds__(NW * 64) void stream_w8a8_kernel(const GemmParams p
     const int g = lane >> 4, mcol = lane & 15;
 
     const int G = gridDim.x, b = blockIdx.x;
-    const int t0 = (int)(((long long)p.T * b) / G);
-    const int t1 = (int)(((long long)p.T * (b + 1)) / G);
+    const int t0 = tile_split(p.T, b, G);
+    const int t1 = tile_split(p.T, b + 1, G);
     const int ntiles = t1 - t0;
 
     unsigned char *xq = lds;                                                          // [SC*4][MP][16]
