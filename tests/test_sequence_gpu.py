@@ -94,6 +94,8 @@ def linear_list(layers, bufs):
     (16, 256, 64, 768, False),
     (32, 256, 64, 1536, False),
     (8, 256, 64, 768, True),
+    (8, 5120, 512, 2560, False),    # 80 steps: five per wave (units padded to eight slots); 320 tiles: one or two per workgroup
+    (4, 1280, 256, 6400, False),    # 20 and 100 steps: uneven shares of one or two and six or seven steps per wave
 ])
 def test_sequence_chain_vs_oracle_and_single_calls(qb, M, hidden, kv, inter, bf16):
     print("sequence", M, hidden, kv, inter, bf16, flush=True)
