@@ -713,7 +713,7 @@ def main() -> int:
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int8 weights x bf16 activations, fp32 accumulate",
+        "dtype": "bf16 (int8 weight codes converted exactly to bf16 in registers, bf16 matrix cores, fp32 accumulate)",
         "data": "synthetic",
         "config": {"workload": f"Qwen3-8B-shaped verification weight stream: {L} layers x 7 int8 linears + fused "
                                f"LM head (V={V}) with greedy acceptance, M={M}, attention excluded",
