@@ -65,6 +65,21 @@ int quasar_version(void);
 int quasar_set_path(int path);
 int quasar_get_path(void);
 
+/* Development knobs (no passage of the paper stands behind them; process-wide, not thread-safe,
+ * meant for launch-shape sweeps in the benchmark, never needed for correct results):
+ *   quasar_set_tuning      waves per workgroup (8 or 16), workgroups per compute unit (1..8) and
+ *                          load-ring depth (4 or 8) of the single-call int8 / bf16 kernels; the
+ *                          first two can also be preset through the environment variables
+ *                          QUASAR_TUNE_NW and QUASAR_TUNE_WGS, read when the library is loaded;
+ *   quasar_set_tuning_w4   waves per workgroup and ring depth of the 4-bit kernel;
+ *   quasar_sequence_set_form   0 (default): quasar_sequence_prepare chooses the kernel form,
+ *                          1: always the form in which every wave both streams and synchronises
+ *                          (A/B timing of the two forms of the whole-step launch).
+ * Each returns QUASAR_ERR_SHAPE for a value outside the stated set. */
+int quasar_set_tuning(int waves, int wgs_per_cu, int depth);
+int quasar_set_tuning_w4(int waves, int depth);
+int quasar_sequence_set_form(int form);
+
 /* Bytes of the packed int8 / packed bf16 weight buffer for an [N, K] matrix.
  * Int8: exactly one byte per parameter (the 2x footprint reduction of Sec. 3.3,
  * "Offline Weight Preparation"); bf16: two.  0 if the shape is invalid. */

@@ -16,6 +16,7 @@
 #include "probe.hpp"
 #include "stream_gemm.hpp"
 #include "stream_sequence.hpp"
+#include "stream_step.hpp"
 #include "sample.hpp"
 #include "stream_w8a8.hpp"
 #include "stream_w4.hpp"
@@ -318,11 +319,9 @@ int quasar_set_path(int path) {
 }
 int quasar_get_path(void) { return g_path.load(); }
 
-/* development knob, not part of the documented contract: waves per workgroup (8 or 16) and
- * workgroups per compute unit (1..8) used by the streaming kernels */
 int quasar_set_tuning(int waves, int wgs_per_cu, int depth) {
     if ((waves != 8 && waves != 16) || wgs_per_cu < 1 || wgs_per_cu > 8 || (depth != 4 && depth != 8))
-        return QUASAR_ERR_DTYPE;
+        return QUASAR_ERR_SHAPE;
     g_tune_nw = waves;
     g_tune_wgs = wgs_per_cu;
     g_tune_d = depth;
@@ -475,10 +474,14 @@ constexpr int kSeqWaves = 16;
 constexpr int kSeqDepth = QUASAR_SEQ_DEPTH;
 constexpr int kSeqMagic = 0x51534551;   // "QSEQ"
 constexpr unsigned int kSeqSpinLimit = 4000000u;
+constexpr unsigned int kStepWaitTicks = 2000000u;   // 20 ms of the 100 MHz clock: bound on any wait of stream_step_kernel
+std::atomic<int> g_seq_form{0};                     // 0: choose, 1: always stream_sequence_kernel
 
 struct SeqHandle {   // lives in quasar_sequence::words
     int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears, a8;
     int n_barriers, n_flag_waits;
+    int split;           // 1: stream_step_kernel (specialised waves), 0: stream_sequence_kernel
+    int split_lds_bytes;
 };
 static_assert(sizeof(SeqHandle) <= sizeof(quasar_sequence), "handle must fit");
 
@@ -658,6 +661,21 @@ int launch_sequence(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
+// Ring depth of the compute waves: 11 waves per compute unit leave each up to 168 registers.
+#ifndef STEP_DEPTH
+#define STEP_DEPTH 24
+#endif
+template <int MP> constexpr int step_depth() { return MP == 32 ? 16 : STEP_DEPTH; }
+
+template <int MP, bool W16>
+int launch_step(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
+    auto kernel = stream_step_kernel<MP, W16, step_depth<MP>()>;
+    if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return QUASAR_ERR_HIP;
+    hipLaunchKernelGGL(sequence_reset_kernel, dim3(1), dim3(64), 0, st, sp.sync);
+    hipLaunchKernelGGL(kernel, dim3(h.grid), dim3(kStepWaves * 64), (unsigned int)h.split_lds_bytes, st, sp);
+    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -700,6 +718,11 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     struct Out { Range r; int ph, seg; long long N, ldy; const uint16_t *y; int writes; };
     std::vector<Out> outs;
     std::vector<Range> reads, writes;     // since the last device-wide barrier
+    // every cache line read so far in the launch (never cleared): a line that some compute unit has
+    // already fetched may sit in a cache with its old contents, so an input that is written inside the
+    // launch AFTER one of its lines was read must be re-read past the caches (barrier form)
+    std::vector<Range> lines_read;
+    auto lines = [](const Range &r) { return Range{r.lo & ~(uintptr_t)127, (r.hi + 127) & ~(uintptr_t)127}; };
     // How does a phase reading `xr` (and writing `yrs`) have to wait?  (see SEQ_WAIT_* in
     // stream_sequence.hpp)  Writes that clash with anything touched since the last barrier, or
     // inputs in buffers written more than once, need the barrier; inputs that are write-once
@@ -712,6 +735,10 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
             for (const Range &rd : reads) if (overlaps(y, rd)) write_clash = true;
         }
         for (const Range &wr : writes) if (overlaps(xr, wr)) raw = true;
+        bool written = raw;
+        for (const Out &o : outs) if (overlaps(lines(xr), lines(o.r))) written = true;
+        if (written)
+            for (const Range &lr : lines_read) if (overlaps(lines(xr), lr)) write_clash = true;
         if (write_clash) return SEQ_WAIT_BARRIER;
         if (!raw) return SEQ_WAIT_NONE;
         int n = 0;
@@ -779,6 +806,7 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
         p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(xr, {yr}, p.producer);
         if (p.wait == SEQ_WAIT_BARRIER) { reads.clear(); writes.clear(); }
         reads.push_back(xr);
+        lines_read.push_back(lines(xr));
         writes.push_back(yr);
         note_output(yr, (int)phases.size(), 0, d.N, d.ldy, d.y);
         phases.push_back(p);
@@ -830,6 +858,55 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     }
     const int lds = xs_max + sc_max + 2 * kSeqWaves * NB * 1024 + acc_max;
     if (lds > kMaxLds) return QUASAR_ERR_SHAPE;
+
+    // ---- the form with specialised waves (stream_step_kernel): bf16 activations, no phase that needs
+    // the device-wide barrier, every flag-gated input a plain column range of at most two earlier
+    // output segments, per-tile flags within the workspace
+    const int split_lds = xs_max + kStepCtrlBytes + kStepNR * kStepNV * NB * 1024 + acc_max;
+    bool split = !a8 && g_seq_form.load() == 0 && split_lds <= kMaxLds;
+    {
+        const long long flag_cap = (long long)(n_linears + 1) * kMaxGrid;
+        long long nflags = 0;
+        for (SeqPhase &p : phases) {
+            if (p.wait == SEQ_WAIT_BARRIER) split = false;
+            p.flag_off = (int)nflags;
+            nflags += p.kind == EPI_ARGMAX ? G : (p.publish ? p.T : 0);
+            if (nflags > flag_cap || nflags >= (1ll << 30)) { split = false; break; }
+        }
+        const int KSTEP = w16 ? kStepK16 : kStepK8;
+        for (size_t pi = 0; split && pi < phases.size(); ++pi) {
+            SeqPhase &p = phases[pi];
+            p.src[0] = p.src[1] = SeqPhase::Src{0, 0, 0, 0};
+            p.fine = 0;
+            if (p.wait != SEQ_WAIT_FLAGS) continue;
+            const uintptr_t xa = reinterpret_cast<uintptr_t>(p.x);
+            const Range xr{xa, reinterpret_cast<uintptr_t>(p.x + (M - 1) * p.ldx + p.K)};
+            int ns = 0;
+            for (const Out &o : outs) {
+                if (!overlaps(xr, o.r)) continue;
+                if ((int)pi <= o.ph || ns == 2 || o.ldy != p.ldx) { split = false; break; }
+                // column k of x is column k - delta of the segment
+                const long long delta = ((long long)reinterpret_cast<uintptr_t>(o.y) - (long long)xa) / 2;
+                if (delta <= -(long long)p.ldx || delta >= (long long)p.ldx) { split = false; break; }
+                const long long k_lo = delta > 0 ? delta : 0;
+                const long long k_hi = delta + o.N < p.K ? delta + o.N : p.K;
+                if (k_hi <= k_lo || (k_lo - delta) % kTileRows) { split = false; break; }
+                const SeqPhase &pp = phases[o.ph];
+                p.src[ns].k_lo = (int)k_lo;
+                p.src[ns].k_hi = (int)k_hi;
+                p.src[ns].flag0 = pp.flag_off + pp.seg[o.seg].tile_begin + (int)((k_lo - delta) / kTileRows);
+                ++ns;
+            }
+            if (!split) break;
+            if (ns == 0) { split = false; break; }
+            // a compute wave's K slice may be fetched as soon as its own producer tiles are done if no
+            // 128-byte line of x holds columns of another slice's producers: rows on line boundaries
+            // (slices are cut at multiples of 32 or 64 columns; the kernel widens them to whole lines),
+            // and at most 64 flags per slice and source
+            const int slice_cols = ((p.SC * kStepVPW + kStepNV - 1) / kStepNV + 1) * KSTEP + 126;
+            p.fine = (xa % 128 == 0 && (p.ldx * 2) % 128 == 0 && slice_cols / kTileRows + 1 <= 64) ? 1 : 0;
+        }
+    }
     if (hipMemcpy(plan_device, phases.data(), phases.size() * sizeof(SeqPhase), hipMemcpyHostToDevice) != hipSuccess)
         return QUASAR_ERR_HIP;
     if (hipMemset(static_cast<unsigned char *>(plan_device) + (size_t)(n_linears + 1) * sizeof(SeqPhase), 0,
@@ -843,12 +920,20 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     h.xs_bytes = xs_max; h.sc_bytes = sc_max; h.lds_bytes = lds < kMinLds ? kMinLds : lds; h.grid = G;
     h.has_verify = verify ? 1 : 0; h.n_linears = (int)n_linears; h.a8 = a8 ? 1 : 0;
     h.n_barriers = 0; h.n_flag_waits = 0;
+    h.split = split ? 1 : 0;
+    h.split_lds_bytes = split_lds < kMinLds ? kMinLds : split_lds;
     for (const SeqPhase &p : phases) {
         if (p.wait == SEQ_WAIT_BARRIER) ++h.n_barriers;
         if (p.wait == SEQ_WAIT_FLAGS) ++h.n_flag_waits;
     }
     std::memset(seq, 0, sizeof(*seq));
     std::memcpy(seq, &h, sizeof(h));
+    return QUASAR_OK;
+}
+
+int quasar_sequence_set_form(int form) {
+    if (form != 0 && form != 1) return QUASAR_ERR_SHAPE;
+    g_seq_form = form;
     return QUASAR_OK;
 }
 
@@ -886,6 +971,20 @@ int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, voi
     sp.zeros = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(plan_device) +
                                                (size_t)(h.n_linears + 1) * sizeof(SeqPhase));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (h.split) {
+        sp.spin_limit = kStepWaitTicks;
+#ifdef STEP_STATS
+        sp.stats = sp.partial + 65536;
+#endif
+        if (h.w16) {
+            if (h.MP == 8) return launch_step<8, true>(h, sp, st);
+            if (h.MP == 16) return launch_step<16, true>(h, sp, st);
+            return launch_step<32, true>(h, sp, st);
+        }
+        if (h.MP == 8) return launch_step<8, false>(h, sp, st);
+        if (h.MP == 16) return launch_step<16, false>(h, sp, st);
+        return launch_step<32, false>(h, sp, st);
+    }
     if (h.w16) {
         if (h.MP == 8) return launch_sequence<8, true, false>(h, sp, st);
         if (h.MP == 16) return launch_sequence<16, true, false>(h, sp, st);
@@ -1009,11 +1108,10 @@ size_t quasar_w4_packed_bytes(int64_t N, int64_t K) {
     return (size_t)(N / kTileRows) * (size_t)(K / kStepK4) * (size_t)kStepBytes4;
 }
 
-/* development knob, not part of the documented contract: waves per workgroup and ring depth (in
- * slots of two steps) of the 4-bit kernels: (16, 4), (16, 2), (8, 8) or (8, 4) */
+/* waves per workgroup and ring depth (in slots of two steps): (16, 4), (16, 2), (8, 8) or (8, 4) */
 int quasar_set_tuning_w4(int waves, int depth) {
     if (!((waves == 16 && (depth == 4 || depth == 2)) || (waves == 8 && (depth == 8 || depth == 4))))
-        return QUASAR_ERR_DTYPE;
+        return QUASAR_ERR_SHAPE;
     g_w4_nw = waves;
     g_w4_d = depth;
     return QUASAR_OK;

@@ -58,9 +58,13 @@ struct SeqPhase {
     int V;
     int producer[2];         // SEQ_WAIT_FLAGS: phases whose completion flags gate this input (-1: unused)
     int publish;             // a later phase waits for this phase's flags
-    int pad_;
+    int flag_off;            // stream_step_kernel: this phase's per-tile flags start here (vocabulary phase: per workgroup)
     const float *smooth;     // W8A8: per-channel smoothing factors of the input ([K], nullptr: none)
-    long long pad2_;
+    // stream_step_kernel, SEQ_WAIT_FLAGS: columns [k_lo, k_hi) of x are rows of an earlier phase's
+    // output segment; the tile that wrote column k raised flag flag0 + (k - k_lo) / 16
+    struct Src { int k_lo, k_hi, flag0, pad; } src[2];
+    int fine;                // rows of x start on 128-byte lines: a K slice may be fetched as soon as its own producers are done
+    int pad_[3];
 };
 
 typedef const __attribute__((address_space(4))) SeqPhase *const_phase_ptr;   // scalar (constant) loads
@@ -83,6 +87,7 @@ struct SeqParams {
     unsigned long long *partial;   // argmax phase: [gridDim.x][MP] packed (logit, index) keys
     unsigned int spin_limit; // bound on polling iterations
     const u32x4 *zeros;      // 1 KB of zeros, never written: what a slot without a weight step loads
+    unsigned long long *stats;   // development builds of stream_step_kernel: per-wave wait totals (nullptr: none)
 };
 
 // Data that crosses from one phase to a later one inside the launch (outputs read as the
