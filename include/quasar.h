@@ -207,7 +207,7 @@ typedef struct quasar_verify_desc {
     int32_t *out_accept_len;  /* device [1] */
 } quasar_verify_desc;
 
-typedef struct quasar_sequence { int32_t words[16]; } quasar_sequence;
+typedef struct quasar_sequence { int32_t words[24]; } quasar_sequence;
 
 size_t quasar_sequence_plan_bytes(int64_t n_linears);
 size_t quasar_sequence_workspace_bytes(int64_t n_linears, int64_t M);

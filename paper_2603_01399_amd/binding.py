@@ -55,7 +55,7 @@ class VerifyDesc(ctypes.Structure):
 
 
 class SequenceHandle(ctypes.Structure):
-    _fields_ = [("words", ctypes.c_int32 * 16)]
+    _fields_ = [("words", ctypes.c_int32 * 24)]
 
 
 

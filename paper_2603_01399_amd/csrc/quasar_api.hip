@@ -29,7 +29,7 @@ namespace {
 
 constexpr int kMaxLds = 160 * 1024;          // gfx950 LDS per compute unit
 constexpr int kSingleChunkX = 128 * 1024;    // activation bytes allowed when K needs no chunking
-constexpr int kMultiChunkX = 96 * 1024;      // activation bytes per chunk otherwise
+constexpr int kMultiChunkX = 64 * 1024;      // activation bytes per chunk otherwise (leaves the whole-step kernel room for its weight queues)
 constexpr int kMinLds = 82 * 1024;           // > half the LDS: at most one workgroup per compute unit
 constexpr int kMaxGrid = 4096;               // bound on workgroups (sizes the argmax partials)
 
@@ -482,6 +482,7 @@ struct SeqHandle {   // lives in quasar_sequence::words
     int n_barriers, n_flag_waits;
     int split;           // 1: stream_step_kernel (specialised waves), 0: stream_sequence_kernel
     int split_lds_bytes;
+    int acc_bytes, queue_steps;
 };
 static_assert(sizeof(SeqHandle) <= sizeof(quasar_sequence), "handle must fit");
 
@@ -862,8 +863,12 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     // ---- the form with specialised waves (stream_step_kernel): bf16 activations, no phase that needs
     // the device-wide barrier, every flag-gated input a plain column range of at most two earlier
     // output segments, per-tile flags within the workspace
-    const int split_lds = xs_max + kStepCtrlBytes + kStepNR * kStepNV * NB * 1024 + acc_max;
-    bool split = !a8 && g_seq_form.load() == 0 && split_lds <= kMaxLds;
+    const int split_fixed = xs_max + kStepCtrlBytes + kStepNR * kStepNV * (MP == 8 ? 512 : NB * 1024) + acc_max;
+    // weight queue per compute wave: a power of two steps, from what the LDS has left
+    int queue_steps = kStepMaxQueue;
+    while (queue_steps >= 2 && split_fixed + queue_steps * kStepNC * 1024 > kMaxLds) queue_steps /= 2;
+    const int split_lds = split_fixed + queue_steps * kStepNC * 1024;
+    bool split = !a8 && g_seq_form.load() == 0 && queue_steps >= 2;
     {
         const long long flag_cap = (long long)(n_linears + 1) * kMaxGrid;
         long long nflags = 0;
@@ -922,6 +927,8 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     h.n_barriers = 0; h.n_flag_waits = 0;
     h.split = split ? 1 : 0;
     h.split_lds_bytes = split_lds < kMinLds ? kMinLds : split_lds;
+    h.acc_bytes = acc_max;
+    h.queue_steps = queue_steps;
     for (const SeqPhase &p : phases) {
         if (p.wait == SEQ_WAIT_BARRIER) ++h.n_barriers;
         if (p.wait == SEQ_WAIT_FLAGS) ++h.n_flag_waits;
@@ -973,6 +980,8 @@ int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, voi
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (h.split) {
         sp.spin_limit = kStepWaitTicks;
+        sp.acc_bytes = h.acc_bytes;
+        sp.queue_steps = h.queue_steps;
 #ifdef STEP_STATS
         sp.stats = sp.partial + 65536;
 #endif

@@ -88,6 +88,8 @@ struct SeqParams {
     unsigned int spin_limit; // bound on polling iterations
     const u32x4 *zeros;      // 1 KB of zeros, never written: what a slot without a weight step loads
     unsigned long long *stats;   // development builds of stream_step_kernel: per-wave wait totals (nullptr: none)
+    int acc_bytes;           // stream_step_kernel: LDS bytes of the running tile sums (phases with K chunks)
+    int queue_steps;         // stream_step_kernel: weight steps per compute wave's LDS queue
 };
 
 // Data that crosses from one phase to a later one inside the launch (outputs read as the

@@ -40,8 +40,11 @@ constexpr int kStepNV = 16;   // K slices (partial sums) per tile
 constexpr int kStepNC = 8;    // compute waves
 constexpr int kStepVPW = kStepNV / kStepNC;
 constexpr int kStepNR = 2;    // reducer waves = staging buffers for partial tiles
-constexpr int kStepNS = 2 + kStepNR;   // service waves: stager, reducers, director
-constexpr int kStepWaves = kStepNC + kStepNS;
+constexpr int kStepNP = 4;    // loader waves
+constexpr int kStepCPP = kStepNC / kStepNP;
+constexpr int kStepNS = 1 + kStepNR;   // service waves: reducers, director
+constexpr int kStepWaves = kStepNC + kStepNP + kStepNS;
+constexpr int kStepMaxQueue = 16;      // steps (KB) per compute wave's queue, at most
 #ifndef STEP_PRIO
 #define STEP_PRIO 3
 #endif
@@ -62,9 +65,11 @@ enum {
     CT_KEYS = CT_ABORT + 1,          // [NR] reducer r has left its argmax keys
     CT_DPROD = CT_KEYS + kStepNR,    // descriptors written per compute wave
     CT_DCONS = CT_DPROD + 1,         // [NC] descriptors compute wave w is done with
-    CT_WORDS = CT_DCONS + kStepNC
+    CT_QHEAD = CT_DCONS + kStepNC,   // [NC] weight steps landed in compute wave w's queue
+    CT_QTAIL = CT_QHEAD + kStepNC,   // [NC] weight steps compute wave w has taken out of it
+    CT_WORDS = CT_QTAIL + kStepNC
 };
-static_assert(CT_WORDS * 4 <= 256, "the control words fit the first 256 bytes of the block");
+static_assert(CT_WORDS * 4 <= 512, "the control words fit the first 512 bytes of the block");
 
 // Control words are accessed through LDS-address-space pointers (a volatile access through a generic
 // pointer would become a flat instruction, which counts as a vector memory operation and would
@@ -102,6 +107,39 @@ __device__ __forceinline__ void load_to_lds_16(unsigned long long gbase, unsigne
                  : "v"(lane_offset), "s"(gbase), "s"(lds_addr)
                  : "memory");   // (M0 is reserved: the compiler keeps nothing in it across statements)
 }
+__device__ __forceinline__ void load_to_lds_16_nt(unsigned long long gbase, unsigned int lane_offset, unsigned int lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                 :
+                 : "v"(lane_offset), "s"(gbase), "s"(lds_addr)
+                 : "memory");
+}
+// up to four consecutive 1 KB steps, global -> consecutive LDS kilobytes: the instruction offset is added to
+// the global AND the LDS address (verified on the device), so one M0 setting serves all of them
+__device__ __forceinline__ void load_steps_to_lds_nt(unsigned int n, unsigned long long gbase, unsigned int lane_offset, unsigned int lds_addr) {
+    switch (n) {
+        case 1: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" : : "v"(lane_offset), "s"(gbase), "s"(lds_addr) : "memory"); break;
+        case 2: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024 nt" : : "v"(lane_offset), "s"(gbase), "s"(lds_addr) : "memory"); break;
+        case 3: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024 nt\n\tglobal_load_lds_dwordx4 %0, %1 offset:2048 nt" : : "v"(lane_offset), "s"(gbase), "s"(lds_addr) : "memory"); break;
+        case 4: asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024 nt\n\tglobal_load_lds_dwordx4 %0, %1 offset:2048 nt\n\tglobal_load_lds_dwordx4 %0, %1 offset:3072 nt" : : "v"(lane_offset), "s"(gbase), "s"(lds_addr) : "memory"); break;
+        default: break;
+    }
+}
+// wait until at most n vector memory operations of this wave are outstanding (n is wave-uniform; the
+// instruction takes an immediate)
+__device__ __forceinline__ void wait_vmcnt_le(unsigned int n) {
+    switch (n) {
+#define QUASAR_VMCNT_CASE(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+        QUASAR_VMCNT_CASE(0) QUASAR_VMCNT_CASE(1) QUASAR_VMCNT_CASE(2) QUASAR_VMCNT_CASE(3) QUASAR_VMCNT_CASE(4)
+        QUASAR_VMCNT_CASE(5) QUASAR_VMCNT_CASE(6) QUASAR_VMCNT_CASE(7) QUASAR_VMCNT_CASE(8) QUASAR_VMCNT_CASE(9)
+        QUASAR_VMCNT_CASE(10) QUASAR_VMCNT_CASE(11) QUASAR_VMCNT_CASE(12) QUASAR_VMCNT_CASE(13) QUASAR_VMCNT_CASE(14)
+        QUASAR_VMCNT_CASE(15) QUASAR_VMCNT_CASE(16) QUASAR_VMCNT_CASE(17) QUASAR_VMCNT_CASE(18) QUASAR_VMCNT_CASE(19)
+        QUASAR_VMCNT_CASE(20) QUASAR_VMCNT_CASE(21) QUASAR_VMCNT_CASE(22) QUASAR_VMCNT_CASE(23) QUASAR_VMCNT_CASE(24)
+        QUASAR_VMCNT_CASE(25) QUASAR_VMCNT_CASE(26) QUASAR_VMCNT_CASE(27) QUASAR_VMCNT_CASE(28) QUASAR_VMCNT_CASE(29)
+        QUASAR_VMCNT_CASE(30) QUASAR_VMCNT_CASE(31) QUASAR_VMCNT_CASE(32)
+#undef QUASAR_VMCNT_CASE
+        default: asm volatile("s_waitcnt vmcnt(32)" ::: "memory"); break;
+    }
+}
 __device__ __forceinline__ unsigned int lds_address_of(const unsigned char *p) {
     return __builtin_amdgcn_readfirstlane(
         (unsigned int)(unsigned long long)((const __attribute__((address_space(3))) unsigned char *)p));
@@ -110,14 +148,13 @@ __device__ __forceinline__ unsigned int lds_address_of(const unsigned char *p) {
 template <int MP, bool W16, int D>
 __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqParams sp) {
     extern __shared__ __align__(16) unsigned char lds[];
-    constexpr int NV = kStepNV, NC = kStepNC, VPW = kStepVPW, NR = kStepNR, RD = kStepRD;
+    constexpr int NV = kStepNV, NC = kStepNC, VPW = kStepVPW, NR = kStepNR, RD = kStepRD, NP = kStepNP, CPP = kStepCPP;
+    constexpr int LB = 4;                        // loads per compute wave and batch of a loader
     constexpr int NB = (MP == 32) ? 2 : 1;
     constexpr int PPS = W16 ? 4 : 8;             // 16-byte LDS pieces per step and token
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
     constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
     constexpr int XSTEP = PPS * MP * 16;         // LDS bytes of one step of activations
-    constexpr int GR = 4;                        // ring slots are refilled in groups of GR
-    static_assert(D % GR == 0, "refill groups tile the ring");
     constexpr unsigned int kForever = 0x7FFFFFFFu;
 
     const int tid = threadIdx.x;
@@ -131,9 +168,15 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
 
     lds_u32 *ctrl = (lds_u32 *)(lds + sp.xs_bytes);
     lds_u32x4 *desc = (lds_u32x4 *)(lds + sp.xs_bytes + 1024);                      // [NC][RD]
-    unsigned long long *keys_lds = reinterpret_cast<unsigned long long *>(lds + sp.xs_bytes + 256);   // [NR][32]
-    f32x4 *stage = reinterpret_cast<f32x4 *>(lds + sp.xs_bytes + kStepCtrlBytes);   // [NR][NV][NB][64]
-    f32x4 *accs = stage + NR * NV * NB * 64;                                        // [tiles][NB][64] (C > 1)
+    unsigned long long *keys_lds = reinterpret_cast<unsigned long long *>(lds + sp.xs_bytes + 512);   // [NR][32]
+    // a partial tile: 16 rows x MP tokens fp32; with MP = 8 only the lanes of tokens 0..7 carry one
+    constexpr int SL = (MP == 8) ? 32 : NB * 64;       // f32x4 entries per partial tile
+    const bool st_lane = MP != 8 || mcol < 8;          // this lane holds part of it ...
+    const int st_idx = MP == 8 ? g * 8 + (mcol & 7) : lane;   // ... at this entry (plus 64 per token block)
+    f32x4 *stage = reinterpret_cast<f32x4 *>(lds + sp.xs_bytes + kStepCtrlBytes);   // [NR][NV][SL]
+    f32x4 *accs = stage + NR * NV * SL;                                             // [tiles][NB][64] (C > 1)
+    const int FW = sp.queue_steps;                                                  // steps per compute wave's weight queue
+    const unsigned int q_off = (unsigned int)(sp.xs_bytes + kStepCtrlBytes + NR * NV * SL * 16 + sp.acc_bytes);   // [NC][FW] KB
 
     if (tid < 256) ctrl[tid] = 0u;
     lds_barrier();
@@ -187,49 +230,14 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
 
     if (w < NC) {
         // =================================================================== compute wave
-        // Both fronts follow the wave's descriptor ring (written by the director wave): one
-        // descriptor per tile of the workgroup, in execution order.
+        // Follows its descriptor ring (one descriptor per tile of the workgroup, written by the director
+        // wave) and takes its weight steps out of its LDS queue, which a loader wave fills.
         const lds_u32x4 *my_desc = desc + w * RD;
-        const unsigned long long zeros = reinterpret_cast<unsigned long long>(sp.zeros);
         auto desc_read = [&](unsigned int i) -> u32x4 {
             const u32x4 v = *reinterpret_cast<const volatile lds_u32x4 *>(my_desc + (i % RD));
             return u32x4{(unsigned int)__builtin_amdgcn_readfirstlane(v.x), (unsigned int)__builtin_amdgcn_readfirstlane(v.y),
                          (unsigned int)__builtin_amdgcn_readfirstlane(v.z), (unsigned int)__builtin_amdgcn_readfirstlane(v.w)};
         };
-        // ---- load front.  It never waits: when the next descriptor has not been written yet (or the
-        // sequence is over) the slot loads a block of zeros and is marked in `dummy`; the compute
-        // front skips marked slots.
-        unsigned int l_i = 0;              // next descriptor to open
-        unsigned long long l_base = zeros;
-        unsigned int l_inc = 0u, l_left = 0u;
-        unsigned int dummy = 0u;           // bit d: ring slot d carries no step
-        bool l_over = false;
-        auto l_open = [&]() -> bool {      // open the next run with steps; false: none available now
-            for (;;) {
-                if (l_over || lds_peek(ctrl + CT_DPROD) <= l_i) return false;
-                const u32x4 dd = desc_read(l_i);
-                if (dd.z >> 16 & DF_END) { l_over = true; return false; }
-                ++l_i;
-                const unsigned int steps = (dd.y >> 16 & 0xFFu) + (dd.y >> 24);
-                if (steps == 0u) continue;
-                l_base = ((unsigned long long)(dd.y & 0xFFFFu) << 32) | dd.x;
-                l_inc = 1024u;
-                l_left = steps;
-                return true;
-            }
-        };
-        unsigned int voff = (unsigned int)lane * 16u;
-        ST_ADD(st_a, lds_wait_ge(ctrl + CT_DPROD, 1u));  // the first descriptor is worth waiting for
-        u32x4 ring[D];
-#pragma unroll
-        for (int d = 0; d < D; ++d) {
-            bool real = l_left > 0u;
-            if (!real) real = l_open();
-            ring[d] = ring_refill_at(real ? l_base : zeros, voff, u32x4{0u, 0u, 0u, 0u});
-            if (real) { l_base += l_inc; --l_left; } else dummy |= 1u << d;
-        }
-
-        // ---- compute front: runs of one K slice (two per tile and wave), a partial tile each
         unsigned int c_i = 0xFFFFFFFFu;  // current descriptor = tile sequence number inside the workgroup
         unsigned int c_useq = 0;         // units finished
         unsigned int c_steps_b = 0, c_flags = 0, c_sa = 0, c_steps_a = 0;
@@ -244,14 +252,84 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
         const unsigned int xlane = (unsigned int)(((W16 ? g : 2 * g) * MP + xm) * 16);
 
         auto post = [&]() {   // the partial tile of slice VPW * w + c_vv of tile c_i
-            f32x4 *st = stage + (((c_i % NR) * NV + (VPW * w + c_vv)) * NB) * 64 + lane;
+            f32x4 *st = stage + ((c_i % NR) * NV + (VPW * w + c_vv)) * SL + st_idx;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                st[nb * 64] = acc[nb];
+                if (st_lane) st[nb * 64] = acc[nb];
                 acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
             lds_drain();
             if (lane == 0) lds_poke(ctrl + CT_POST + (c_i % NR) * NV + VPW * w + c_vv, c_i / NR + 1u);
+        };
+        // First tile of a unit: bring this wave's K slice of the activations into LDS.  The wave has no
+        // other memory traffic of its own, so what it waits for here is exactly its producers and its
+        // own loads.  `info`: phase | chunk << 16 | (compute waves whose slice of the previous unit
+        // overlaps this slice in LDS) << 24.
+        const unsigned int lds_base = lds_address_of(lds);
+        auto stage_slice = [&](unsigned int info) {
+            const auto &P = phases[info & 0xFFFFu];
+            const int c = info >> 16 & 0xFF;
+            const unsigned int need = info >> 24;
+            const int scc = min(P.SC, P.S - c * P.SC);
+            const int k0 = c * P.SC * KSTEP;
+            const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+            bool aborted = lds_peek(ctrl + CT_ABORT) != 0u;
+            // ---- the LDS bytes are free: the waves that read them in the previous unit have left it
+            for (int spin = 0; !aborted; ++spin) {
+                static_assert(NC == 8, "the eight counters are read with two 16-byte loads");
+                const u32x4 f0 = *reinterpret_cast<const volatile lds_u32x4 *>(ctrl + CT_FREED);
+                const u32x4 f1 = *reinterpret_cast<const volatile lds_u32x4 *>(ctrl + CT_FREED + 4);
+                const unsigned int fr[NC] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+                unsigned int left = 0;
+#pragma unroll
+                for (int cw = 0; cw < NC; ++cw)
+                    if ((unsigned int)__builtin_amdgcn_readfirstlane(fr[cw]) >= c_useq) left |= 1u << cw;
+                if ((left & need) == need) break;
+                __builtin_amdgcn_s_sleep(STEP_SLEEP);
+                if (lds_peek(ctrl + CT_ABORT) || (unsigned int)(__builtin_amdgcn_s_memrealtime() - t0) > t_limit) aborted = true;
+            }
+            // ---- the producers of the slice have raised their flags
+            if (P.wait == SEQ_WAIT_FLAGS && !aborted) {
+                const int nsrc = P.src[1].k_hi > P.src[1].k_lo ? 2 : 1;
+                for (int s = 0; s < nsrc && !aborted; ++s) {
+                    int ka = 0, kb = P.K;
+                    if (P.fine) {   // all columns of every 128-byte line the slice touches
+                        ka = (k0 + (scc * (VPW * w)) / NV * KSTEP) & ~63;
+                        kb = (k0 + (scc * (VPW * w + VPW)) / NV * KSTEP + 63) & ~63;
+                    }
+                    const int lo = max(ka, P.src[s].k_lo), hi = min(kb, P.src[s].k_hi);
+                    const int fa = P.src[s].flag0 + ((lo - P.src[s].k_lo) >> 4);
+                    const int nf = hi > lo ? ((hi - P.src[s].k_lo + 15) >> 4) - ((lo - P.src[s].k_lo) >> 4) : 0;
+                    for (int f0 = 0; f0 < nf && !aborted; f0 += 64) {
+                        for (;;) {
+                            const unsigned int f = f0 + lane < nf ? coherent_load_u32(sp.flags + fa + f0 + lane) : epoch;
+                            const unsigned int err = coherent_load_u32(&sp.sync[1]);
+                            if (__builtin_amdgcn_ballot_w64(f != epoch) == 0ull) break;
+                            if (err != 0u || lds_peek(ctrl + CT_ABORT) || (unsigned int)(__builtin_amdgcn_s_memrealtime() - t0) > t_limit) { aborted = true; break; }
+                            __builtin_amdgcn_s_sleep(STEP_SLEEP);
+                        }
+                    }
+                }
+            }
+            if (aborted) {
+                lds_poke(ctrl + CT_ABORT, 1u);
+                if (lane == 0) coherent_store_u32(&sp.sync[1], 1u);
+                return;
+            }
+            // ---- piece i0 + lane: token (lane % MP), columns k0 + 8 (i0 / MP + lane / MP) ..
+            const unsigned int x_voff = (unsigned int)min(lane & (MP - 1), M - 1) * (unsigned int)P.ldx * 2u + 16u * (unsigned int)(lane >> LMP);
+            const int pa = (scc * (VPW * w)) / NV * (PPS * MP);
+            const int pb = (scc * (VPW * w + VPW)) / NV * (PPS * MP);
+            unsigned long long gbase = reinterpret_cast<unsigned long long>(P.x) + 2ull * (unsigned long long)(k0 + 8 * (pa >> LMP));
+            unsigned int laddr = lds_base + (unsigned int)pa * 16u;
+            for (int i0 = pa; i0 < pb; i0 += 64) {
+                if (i0 + 64 <= pb) load_to_lds_16(gbase, x_voff, laddr);
+                else if (i0 + lane < pb) load_to_lds_16(gbase, x_voff, laddr);
+                gbase += 1024u / MP;   // 64 / MP pieces of 8 columns, 2 bytes each, per token
+                laddr += 1024u;
+            }
+            vmem_drain();
+            ST_ADD(st_b, (unsigned int)(__builtin_amdgcn_s_memrealtime() - t0));
         };
         // move to the next slice that has steps (slices without steps post nothing: the reducer knows)
         auto c_next = [&]() {
@@ -270,8 +348,18 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
                 }
                 ++c_i;
                 if (lane == 0) lds_poke(ctrl + CT_DCONS + w, c_i);
-                ST_ADD(st_a, lds_wait_ge(ctrl + CT_DPROD, c_i + 1u));
-                const u32x4 dd = desc_read(c_i);
+                // one LDS round trip in the usual case: the descriptor together with the two counters
+                // that may hold the tile up; the waits below re-read only what was not there yet
+                u32x4 dv = *reinterpret_cast<const volatile lds_u32x4 *>(my_desc + (c_i % RD));
+                const unsigned int v_prod = *reinterpret_cast<const volatile lds_u32 *>(ctrl + CT_DPROD);
+                const unsigned int v_cons = *reinterpret_cast<const volatile lds_u32 *>(ctrl + CT_CONS + (c_i % NR));
+                const unsigned int s_prod = __builtin_amdgcn_readfirstlane(v_prod), s_cons = __builtin_amdgcn_readfirstlane(v_cons);
+                u32x4 dd = u32x4{(unsigned int)__builtin_amdgcn_readfirstlane(dv.x), (unsigned int)__builtin_amdgcn_readfirstlane(dv.y),
+                                 (unsigned int)__builtin_amdgcn_readfirstlane(dv.z), (unsigned int)__builtin_amdgcn_readfirstlane(dv.w)};
+                if (s_prod < c_i + 1u) {
+                    ST_ADD(st_a, lds_wait_ge(ctrl + CT_DPROD, c_i + 1u));
+                    dd = desc_read(c_i);
+                }
                 c_flags = dd.z >> 16;
                 if (c_flags & DF_END) { done = true; c_left = 0u; c_flags = 0u; return; }
                 c_steps_a = dd.y >> 16 & 0xFFu;
@@ -279,9 +367,9 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
                 c_sa = dd.z & 0xFFFFu;
                 c_vv = 0;
                 if (c_steps_a + c_steps_b > 0u) {
-                    if (c_flags & DF_FIRST) ST_ADD(st_b, lds_wait_ge(ctrl + CT_READY + w, c_useq + 1u));
+                    if (c_flags & DF_FIRST) stage_slice(dd.w);
                     // staging buffer c_i % NR is free once the tile that used it before has been read
-                    ST_ADD(st_c, lds_wait_ge(ctrl + CT_CONS + (c_i % NR), c_i / NR));
+                    if (s_cons < c_i / NR) ST_ADD(st_c, lds_wait_ge(ctrl + CT_CONS + (c_i % NR), c_i / NR));
                 }
                 if (c_steps_a > 0u) {
                     c_left = c_steps_a;
@@ -292,52 +380,172 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
         };
         c_next();
 
-        for (;;) {
-            if (done) break;
+        const unsigned char *my_q = lds + q_off + (unsigned int)(w * FW) * 1024u + (unsigned int)lane * 16u;
+        const unsigned int qmask = (unsigned int)FW - 1u;   // FW is a power of two
+        unsigned int taken = 0;          // weight steps taken out of the queue
+        unsigned int avail = 0;          // steps known to have landed
+        auto fetch = [&](unsigned int step, unsigned int xoff, u32x4 &wv, u32x4 (&bb)[NB][2]) {
+            wv = *reinterpret_cast<const u32x4 *>(my_q + (step & qmask) * 1024u);
+            const unsigned char *xp = lds + (xlane + xoff);
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
-                const u32x4 wv = ring[d];
-                if (dummy >> d & 1u) ST_ADD(st_d, 1u);
-                if (!(dummy >> d & 1u)) {
-                    const unsigned char *xp = lds + (xlane + c_xoff);
-                    c_xoff += (unsigned int)XSTEP;
-                    bf16x8 a0, a1;
-                    if constexpr (!W16) {
-                        a0 = codes_to_bf16x8(wv.x, wv.y);
-                        a1 = codes_to_bf16x8(wv.z, wv.w);
-                    } else {
-                        a0 = __builtin_bit_cast(bf16x8, wv);
-                    }
+            for (int nb = 0; nb < NB; ++nb) {
+                bb[nb][0] = *reinterpret_cast<const u32x4 *>(xp + nb * 256);
+                if constexpr (!W16) bb[nb][1] = *reinterpret_cast<const u32x4 *>(xp + nb * 256 + MP * 16);
+            }
+        };
+        while (!done) {
+            if (avail == 0u) {
+                ST_ADD(st_d, lds_wait_ge(ctrl + CT_QHEAD + w, taken + 1u));
+                avail = lds_peek(ctrl + CT_QHEAD + w) - taken;
+                if (avail == 0u) avail = 1u;   // (only after an abort)
+            }
+            const unsigned int n = min(avail, c_left);
+            // operands of a step are requested from LDS while the step before it is multiplied
+#ifdef STEP_STATS
+            const unsigned long long ti0 = __builtin_amdgcn_s_memrealtime();
+#endif
+            u32x4 wv, bb[NB][2];
+            fetch(taken, c_xoff, wv, bb);
+            for (unsigned int i = 0; i < n; ++i) {
+                u32x4 wn = wv, bn[NB][2];
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const u32x4 b0 = *reinterpret_cast<const u32x4 *>(xp + nb * 256);
-                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb], 0, 0, 0);
-                        if constexpr (!W16) {
-                            const u32x4 b1 = *reinterpret_cast<const u32x4 *>(xp + nb * 256 + MP * 16);
-                            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1), acc[nb], 0, 0, 0);
-                        }
-                    }
-                    if (__builtin_expect(--c_left == 0u, 0)) {
-                        post();
-                        c_next();
-                    }
+                for (int nb = 0; nb < NB; ++nb) { bn[nb][0] = bb[nb][0]; bn[nb][1] = bb[nb][1]; }
+                if (i + 1u < n) fetch(taken + i + 1u, c_xoff + (i + 1u) * (unsigned int)XSTEP, wn, bn);
+                bf16x8 a0, a1;
+                if constexpr (!W16) {
+                    a0 = codes_to_bf16x8(wv.x, wv.y);
+                    a1 = codes_to_bf16x8(wv.z, wv.w);
+                } else {
+                    a0 = __builtin_bit_cast(bf16x8, wv);
                 }
-                if ((d & (GR - 1)) == GR - 1) {
 #pragma unroll
-                    for (int e = d - (GR - 1); e <= d; ++e) {
-                        bool real = l_left > 0u;
-                        if (__builtin_expect(!real, 0)) real = l_open();
-                        ring[e] = ring_refill_at(real ? l_base : zeros, voff, ring[e]);
-                        if (real) { l_base += l_inc; --l_left; dummy &= ~(1u << e); } else dummy |= 1u << e;
-                    }
+                for (int nb = 0; nb < NB; ++nb) {
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, bb[nb][0]), acc[nb], 0, 0, 0);
+                    if constexpr (!W16)
+                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, bb[nb][1]), acc[nb], 0, 0, 0);
                 }
+                wv = wn;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) { bb[nb][0] = bn[nb][0]; bb[nb][1] = bn[nb][1]; }
+            }
+            taken += n;
+            avail -= n;
+            c_left -= n;
+            c_xoff += n * (unsigned int)XSTEP;
+            lds_drain();                 // the queue entries have been read: the loader may reuse them
+#ifdef STEP_STATS
+            st_e += (unsigned int)(__builtin_amdgcn_s_memrealtime() - ti0);
+            st_f += 1u;
+#endif
+            if (lane == 0) lds_poke(ctrl + CT_QTAIL + w, taken);
+            if (c_left == 0u) {
+                post();
+                c_next();
             }
         }
         stats_out();
         return;
     }
 
-    if (w == NC + 1 + NR) {
+    if (w < NC + NP) {
+        // =================================================================== loader
+        // Streams the weight steps of its CPP compute waves, in their order, into their LDS queues with
+        // direct-to-LDS loads.  It is the only kind of wave that waits for HBM: a compute wave that is
+        // held up (activations not there yet) leaves its queue filling, and the queue empties at compute
+        // speed afterwards.  Loads go out in batches; a batch is known to have landed (loads return in
+        // order) once no more loads are outstanding than were issued after it.
+        const int p = w - NC;
+        const unsigned int lds_base = lds_address_of(lds);
+        const unsigned int voff = (unsigned int)lane * 16u;
+        const unsigned int qmask = (unsigned int)FW - 1u;   // FW is a power of two
+        static_assert(CPP == 2, "the tails of a loader's compute waves are read with one 8-byte load");
+        unsigned int d_i[CPP], left[CPP], issued[CPP], head[CPP];
+        unsigned long long base[CPP];
+        bool over[CPP];
+#pragma unroll
+        for (int j = 0; j < CPP; ++j) { d_i[j] = 0; left[j] = 0; issued[j] = 0; head[j] = 0; base[j] = 0; over[j] = false; }
+        unsigned int q0 = 0, q1 = 0, q2 = 0;     // batches in flight, oldest first: loads per compute wave, 8 bits each
+        int nq = 0;
+        unsigned int prod = 0;                   // descriptors known to have been written
+        auto total = [](unsigned int q) { return (q & 0xFFu) + (q >> 8 & 0xFFu) + (q >> 16 & 0xFFu) + (q >> 24); };
+        for (;;) {
+            const u32x2 tv = *reinterpret_cast<const volatile __attribute__((address_space(3))) u32x2 *>(ctrl + CT_QTAIL + p * CPP);
+            const unsigned int tails[CPP] = {(unsigned int)__builtin_amdgcn_readfirstlane(tv.x), (unsigned int)__builtin_amdgcn_readfirstlane(tv.y)};
+            unsigned int batch = 0;
+#pragma unroll
+            for (int j = 0; j < CPP; ++j) {
+                const int cw = p * CPP + j;
+                const unsigned int room = (unsigned int)FW - (issued[j] - tails[j]);
+                if (left[j] == 0u && room > 0u && !over[j]) {
+                    // open the wave's next run with steps, if its descriptor has been written
+                    for (;;) {
+                        if (prod <= d_i[j]) prod = lds_peek(ctrl + CT_DPROD);
+                        if (prod <= d_i[j]) break;
+                        const u32x4 v = *reinterpret_cast<const volatile lds_u32x4 *>(desc + cw * RD + (d_i[j] % RD));
+                        const unsigned int dy = __builtin_amdgcn_readfirstlane(v.y), dz = __builtin_amdgcn_readfirstlane(v.z);
+                        if (dz >> 16 & DF_END) { over[j] = true; break; }
+                        ++d_i[j];
+                        left[j] = (dy >> 16 & 0xFFu) + (dy >> 24);
+                        base[j] = ((unsigned long long)(dy & 0xFFFFu) << 32) | (unsigned int)__builtin_amdgcn_readfirstlane(v.x);
+                        if (left[j]) break;
+                    }
+                }
+                const unsigned int k = min(min(room, left[j]), (unsigned int)LB);
+                const unsigned int q_addr = lds_base + q_off + (unsigned int)(cw * FW) * 1024u;
+                // (the queue is a ring: up to the wrap, then the rest)
+                const unsigned int at = issued[j] & qmask;
+                const unsigned int k1 = min(k, (unsigned int)FW - at);
+                load_steps_to_lds_nt(k1, base[j], voff, q_addr + at * 1024u);
+                load_steps_to_lds_nt(k - k1, base[j] + k1 * 1024ull, voff, q_addr);
+                base[j] += k * 1024ull;
+                issued[j] += k;
+                left[j] -= k;
+                batch |= k << (8 * j);
+            }
+            if (batch) {
+                if (nq == 0) q0 = batch; else if (nq == 1) q1 = batch; else q2 = batch;
+                ++nq;
+            }
+            if (nq == 3 || (batch == 0u && nq > 0)) {
+                // the oldest batch has landed once only the younger ones are outstanding
+#ifdef STEP_STATS
+                const unsigned long long tw0 = __builtin_amdgcn_s_memrealtime();
+#endif
+                wait_vmcnt_le((nq > 1 ? total(q1) : 0u) + (nq > 2 ? total(q2) : 0u));
+#ifdef STEP_STATS
+                st_a += (unsigned int)(__builtin_amdgcn_s_memrealtime() - tw0);
+                st_c += total(q0);
+                ++st_d;
+#endif
+#pragma unroll
+                for (int j = 0; j < CPP; ++j) {
+                    const unsigned int k = q0 >> (8 * j) & 0xFFu;
+                    if (k) {
+                        head[j] += k;
+                        if (lane == 0) lds_poke(ctrl + CT_QHEAD + p * CPP + j, head[j]);
+                    }
+                }
+                q0 = q1; q1 = q2; q2 = 0;
+                --nq;
+            } else if (batch == 0u) {
+                bool all_over = true;
+#pragma unroll
+                for (int j = 0; j < CPP; ++j) all_over = all_over && over[j];
+                if (all_over || lds_peek(ctrl + CT_ABORT)) break;
+#ifdef STEP_STATS
+                const unsigned long long ts0 = __builtin_amdgcn_s_memrealtime();
+#endif
+                __builtin_amdgcn_s_sleep(STEP_SLEEP);
+#ifdef STEP_STATS
+                st_b += (unsigned int)(__builtin_amdgcn_s_memrealtime() - ts0);
+#endif
+            }
+        }
+        stats_out();
+        return;
+    }
+
+    if (w == NC + NP + NR) {
         // =================================================================== director
         // Writes, for every tile of the workgroup in execution order, one descriptor per compute wave
         // (lane = compute wave): address of the wave's first weight step of the tile, steps of its two
@@ -361,6 +569,7 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
             ++prod;
             if (lane == 0) lds_poke(ctrl + CT_DPROD, prod);
         };
+        int prev_scc = 0;            // steps of the previous unit (its slices' LDS ranges follow from it)
         for (int ph = 0; ph < nph; ++ph) {
             const auto &P = phases[ph];
             const int ntiles = tiles_of(P);
@@ -368,6 +577,13 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
             for (int c = 0; c < P.C; ++c) {
                 const int scc = min(P.SC, P.S - c * P.SC);
                 const int sa = (scc * (VPW * cw)) / NV, sm = (scc * (VPW * cw + 1)) / NV, se = (scc * (VPW * cw + VPW)) / NV;
+                // compute waves whose slice of the previous unit overlaps this wave's slice of this one in LDS
+                unsigned int need = 0;
+#pragma unroll
+                for (int pw = 0; pw < NC; ++pw)
+                    if ((prev_scc * (VPW * pw)) / NV < se && (prev_scc * (VPW * pw + VPW)) / NV > sa) need |= 1u << pw;
+                prev_scc = scc;
+                const unsigned int info = (unsigned int)ph | ((unsigned int)c << 16) | (need << 24);
                 for (int tl = 0; tl < ntiles; ++tl) {
                     const int t = b + tl * G;
                     const int s = seg_of(P, t);
@@ -376,7 +592,7 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
                     const unsigned int fl = (tl == 0 ? DF_FIRST : 0u) | (tl == ntiles - 1 ? DF_LAST : 0u);
                     emit(u32x4{(unsigned int)base,
                                (unsigned int)(base >> 32) | ((unsigned int)(sm - sa) << 16) | ((unsigned int)(se - sm) << 24),
-                               (unsigned int)sa | (fl << 16), 0u});
+                               (unsigned int)sa | (fl << 16), info});
                 }
             }
         }
@@ -385,156 +601,8 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
     }
 
     __builtin_amdgcn_s_setprio(STEP_PRIO);
-    if (w == NC) {
-        // =================================================================== stager
-        const unsigned int lds_base = lds_address_of(lds);
-        unsigned int useq = 0;
-        bool aborted = false;
-        int prev_scc = 0;            // steps of the previous unit (its slices' LDS byte ranges follow from it)
-#ifdef STEP_STATS
-        unsigned long long t_prev = 0;
-#endif
-        for (int ph = 0; ph < nph; ++ph) {
-            const auto &P = phases[ph];
-            if (tiles_of(P) == 0) continue;
-            int nsrc = P.wait == SEQ_WAIT_FLAGS ? (P.src[1].k_hi > P.src[1].k_lo ? 2 : 1) : 0;
-            if (nsrc > 0 && !P.fine) {
-                // rows of x do not start on cache-line boundaries: a line may only be fetched when
-                // everything in it has been produced, so wait for all producer tiles first
-                const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
-                for (int s = 0; s < nsrc && !aborted; ++s) {
-                    const int nfl = (P.src[s].k_hi - P.src[s].k_lo + 15) >> 4;
-                    for (int f0 = 0; f0 < nfl && !aborted; f0 += 64) {
-                        for (;;) {
-                            const unsigned int f = f0 + lane < nfl ? coherent_load_u32(sp.flags + P.src[s].flag0 + f0 + lane) : epoch;
-                            if (__builtin_amdgcn_ballot_w64(f != epoch) == 0ull) break;
-                            if (lds_peek(ctrl + CT_ABORT) || coherent_load_u32(&sp.sync[1]) != 0u) { aborted = true; break; }
-                            if (__builtin_amdgcn_s_memrealtime() - t0 > t_limit) {
-                                aborted = true;
-                                lds_poke(ctrl + CT_ABORT, 1u);
-                                if (lane == 0) coherent_store_u32(&sp.sync[1], 1u);
-                                break;
-                            }
-                            __builtin_amdgcn_s_sleep(STEP_SLEEP);
-                        }
-                    }
-                }
-                nsrc = 0;
-            }
-            // this lane's share of a 64-piece load: row of its token, 8 columns per piece
-            const unsigned int x_voff = (unsigned int)min(lane & (MP - 1), M - 1) * (unsigned int)P.ldx * 2u + 16u * (unsigned int)(lane >> LMP);
-            for (int c = 0; c < P.C; ++c, ++useq) {
-                const int scc = min(P.SC, P.S - c * P.SC);
-                const int k0 = c * P.SC * KSTEP;
-                unsigned int pending = (1u << NC) - 1u;
-                unsigned long long t0 = 0;
-                bool timing = false;
-                while (pending) {
-                    // ---- slices whose LDS bytes nobody reads any more: every compute wave whose slice of
-                    // the PREVIOUS unit overlaps them has left that unit (the same wave when K is the same)
-                    unsigned int left = 0;
-#pragma unroll
-                    for (int cw = 0; cw < NC; ++cw)
-                        if (aborted || lds_peek(ctrl + CT_FREED + cw) >= useq) left |= 1u << cw;
-                    unsigned int cand = 0;
-#pragma unroll
-                    for (int cw = 0; cw < NC; ++cw) {
-                        const int a = (scc * (VPW * cw)) / NV, e = (scc * (VPW * cw + VPW)) / NV;   // in steps
-                        unsigned int need = 1u << cw;
-#pragma unroll
-                        for (int pw = 0; pw < NC; ++pw)
-                            if ((prev_scc * (VPW * pw)) / NV < e && (prev_scc * (VPW * pw + VPW)) / NV > a) need |= 1u << pw;
-                        if ((pending >> cw & 1u) && (left & need) == need) cand |= 1u << cw;
-                    }
-                    // ---- of those, the ones whose producers have raised their flags
-                    unsigned int go = cand;
-                    if (nsrc > 0 && cand && !aborted) {
-                        unsigned int fl[NC][2];
-#pragma unroll
-                        for (int cw = 0; cw < NC; ++cw) {
-#pragma unroll
-                            for (int s = 0; s < 2; ++s) {
-                                fl[cw][s] = epoch;
-                                if (s < nsrc && (cand >> cw & 1u)) {
-                                    // all columns of every 128-byte line the slice touches
-                                    const int ka = (k0 + (scc * (VPW * cw)) / NV * KSTEP) & ~63;
-                                    const int kb = (k0 + (scc * (VPW * cw + VPW)) / NV * KSTEP + 63) & ~63;
-                                    const int lo = max(ka, P.src[s].k_lo), hi = min(kb, P.src[s].k_hi);
-                                    const int fa = P.src[s].flag0 + ((lo - P.src[s].k_lo) >> 4);
-                                    const int nf = hi > lo ? ((hi - P.src[s].k_lo + 15) >> 4) - ((lo - P.src[s].k_lo) >> 4) : 0;
-                                    // (the host keeps nf <= 64 whenever this path is taken)
-                                    if (lane < nf) fl[cw][s] = coherent_load_u32(sp.flags + fa + lane);
-                                }
-                            }
-                        }
-                        const unsigned int err = coherent_load_u32(&sp.sync[1]);
-#pragma unroll
-                        for (int cw = 0; cw < NC; ++cw) {
-                            const bool ok = fl[cw][0] == epoch && fl[cw][1] == epoch;
-                            if (__builtin_amdgcn_ballot_w64(!ok) != 0ull) go &= ~(1u << cw);
-                        }
-                        if (err) aborted = true;
-                    }
-                    if (aborted) go = pending;
-                    // ---- move their slices
-                    if (go) {
-#ifdef STEP_STATS
-                        const unsigned long long tl0 = __builtin_amdgcn_s_memrealtime();
-#endif
-                        if (!aborted) {
-                            for (int cw = 0; cw < NC; ++cw) {
-                                if (!(go >> cw & 1u)) continue;
-                                const int pa = (scc * (VPW * cw)) / NV * (PPS * MP);
-                                const int pb = (scc * (VPW * cw + VPW)) / NV * (PPS * MP);
-                                // piece i0 + lane: token (lane % MP), columns k0 + 8 (i0 / MP + lane / MP) ..
-                                unsigned long long gbase = reinterpret_cast<unsigned long long>(P.x) +
-                                                           2ull * (unsigned long long)(k0 + 8 * (pa >> LMP));
-                                unsigned int laddr = lds_base + (unsigned int)pa * 16u;
-                                for (int i0 = pa; i0 < pb; i0 += 64) {
-                                    if (i0 + 64 <= pb) load_to_lds_16(gbase, x_voff, laddr);
-                                    else if (i0 + lane < pb) load_to_lds_16(gbase, x_voff, laddr);
-                                    gbase += 1024u / MP;   // 64 / MP pieces of 8 columns, 2 bytes each, per token
-                                    laddr += 1024u;
-                                }
-                            }
-                            vmem_drain();
-                        }
-#ifdef STEP_STATS
-                        st_c += (unsigned int)(__builtin_amdgcn_s_memrealtime() - tl0);
-                        ++st_d;
-#endif
-                        if (lane == 0) {
-                            for (int cw = 0; cw < NC; ++cw)
-                                if (go >> cw & 1u) lds_poke(ctrl + CT_READY + cw, useq + 1u);
-                        }
-                        lds_drain();
-                        pending &= ~go;
-                        timing = false;
-                    } else {
-#ifdef STEP_STATS
-                        if (timing) { if (cand) st_b += (unsigned int)(__builtin_amdgcn_s_memrealtime() - t_prev); else st_a += (unsigned int)(__builtin_amdgcn_s_memrealtime() - t_prev); }
-                        t_prev = __builtin_amdgcn_s_memrealtime();
-#endif
-                        if (lds_peek(ctrl + CT_ABORT)) aborted = true;
-                        if (!timing) { t0 = __builtin_amdgcn_s_memrealtime(); timing = true; }
-                        else if (__builtin_amdgcn_s_memrealtime() - t0 > t_limit) {
-                            aborted = true;
-                            lds_poke(ctrl + CT_ABORT, 1u);
-                            if (lane == 0) coherent_store_u32(&sp.sync[1], 1u);
-                        }
-                        __builtin_amdgcn_s_sleep(STEP_SLEEP);
-                    }
-                }
-                prev_scc = scc;
-            }
-        }
-        report_abort();
-        stats_out();
-        return;
-    }
-
     // ======================================================================= reducer
-    const int r = w - NC - 1;
+    const int r = w - NC - NP;
     float bestv[NB];
     unsigned int besti[NB];
 #pragma unroll
@@ -563,17 +631,28 @@ __global__ __launch_bounds__(kStepWaves * 64) void stream_step_kernel(const SeqP
 #pragma unroll
                 for (int v = 0; v < NV; ++v)
                     if ((scc * (v + 1)) / NV > (scc * v) / NV) live |= 1u << v;
-#pragma unroll
-                for (int v = 0; v < NV; ++v)
-                    if (live >> v & 1u) ST_ADD(st_a, lds_wait_ge(ctrl + CT_POST + r * NV + v, n / NR + 1u));
-                const f32x4 *st = stage + (r * NV * NB) * 64 + lane;
+                {   // lane v < 16 watches slice v's counter: one LDS round trip per look
+                    const unsigned int need = n / NR + 1u;
+                    const bool mine = lane < NV && (live >> lane & 1u);
+                    unsigned long long t0 = 0;
+                    for (int spin = 0;; ++spin) {
+                        const unsigned int seen = *reinterpret_cast<const volatile lds_u32 *>(ctrl + CT_POST + r * NV + (lane & (NV - 1)));
+                        if (__builtin_amdgcn_ballot_w64(mine && seen < need) == 0ull) break;
+                        if (spin == 0) t0 = __builtin_amdgcn_s_memrealtime();
+                        __builtin_amdgcn_s_sleep(STEP_SLEEP);
+                        if (lds_peek(ctrl + CT_ABORT)) break;
+                        if ((unsigned int)(__builtin_amdgcn_s_memrealtime() - t0) > t_limit) { lds_poke(ctrl + CT_ABORT, 1u); break; }
+                    }
+                    if (t0) ST_ADD(st_a, (unsigned int)(__builtin_amdgcn_s_memrealtime() - t0));
+                }
+                const f32x4 *st = stage + (r * NV) * SL + st_idx;
                 f32x4 rsum[NB];
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     rsum[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int v = 0; v < NV; ++v)
-                        if (live >> v & 1u) rsum[nb] += st[(v * NB + nb) * 64];
+                        if ((live >> v & 1u) && st_lane) rsum[nb] += st[v * SL + nb * 64];
                 }
                 lds_drain();
                 if (lane == 0) lds_poke(ctrl + CT_CONS + r, n / NR + 1u);
