@@ -71,14 +71,10 @@ int quasar_get_path(void);
  *                          load-ring depth (4 or 8) of the single-call int8 / bf16 kernels; the
  *                          first two can also be preset through the environment variables
  *                          QUASAR_TUNE_NW and QUASAR_TUNE_WGS, read when the library is loaded;
- *   quasar_set_tuning_w4   waves per workgroup and ring depth of the 4-bit kernel;
- *   quasar_sequence_set_form   0 (default): quasar_sequence_prepare chooses the kernel form,
- *                          1: always the form in which every wave both streams and synchronises
- *                          (A/B timing of the two forms of the whole-step launch).
+ *   quasar_set_tuning_w4   waves per workgroup and ring depth of the 4-bit kernel.
  * Each returns QUASAR_ERR_SHAPE for a value outside the stated set. */
 int quasar_set_tuning(int waves, int wgs_per_cu, int depth);
 int quasar_set_tuning_w4(int waves, int depth);
-int quasar_sequence_set_form(int form);
 
 /* Bytes of the packed int8 / packed bf16 weight buffer for an [N, K] matrix.
  * Int8: exactly one byte per parameter (the 2x footprint reduction of Sec. 3.3,
@@ -207,7 +203,7 @@ typedef struct quasar_verify_desc {
     int32_t *out_accept_len;  /* device [1] */
 } quasar_verify_desc;
 
-typedef struct quasar_sequence { int32_t words[24]; } quasar_sequence;
+typedef struct quasar_sequence { int32_t words[16]; } quasar_sequence;
 
 size_t quasar_sequence_plan_bytes(int64_t n_linears);
 size_t quasar_sequence_workspace_bytes(int64_t n_linears, int64_t M);

@@ -21,7 +21,7 @@ PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 # every symbol declared in include/quasar.h
 EXPORTS = (
     "quasar_status_string", "quasar_version", "quasar_set_path", "quasar_get_path",
-    "quasar_set_tuning", "quasar_set_tuning_w4", "quasar_sequence_set_form",
+    "quasar_set_tuning", "quasar_set_tuning_w4",
     "quasar_packed_bytes", "quasar_packed_bytes_bf16", "quasar_workspace_bytes",
     "quasar_quantize_weights", "quasar_unpack_weights", "quasar_w8_linear", "quasar_lmhead_verify",
     "quasar_pack_bf16_weights", "quasar_bf16_linear", "quasar_bf16_lmhead_verify",
@@ -55,7 +55,7 @@ class VerifyDesc(ctypes.Structure):
 
 
 class SequenceHandle(ctypes.Structure):
-    _fields_ = [("words", ctypes.c_int32 * 24)]
+    _fields_ = [("words", ctypes.c_int32 * 16)]
 
 
 
@@ -79,7 +79,6 @@ def _load() -> ctypes.CDLL:
     lib.quasar_set_path.argtypes = [ci]
     lib.quasar_get_path.argtypes = []
     lib.quasar_set_tuning.argtypes = [ci, ci, ci]
-    lib.quasar_sequence_set_form.argtypes = [ci]
     for name in ("quasar_packed_bytes", "quasar_packed_bytes_bf16"):
         getattr(lib, name).argtypes = [i64, i64]
         getattr(lib, name).restype = sz
@@ -182,11 +181,6 @@ def get_path() -> int:
 
 def set_tuning(waves: int, wgs_per_cu: int, depth: int = 8) -> None:
     _check("quasar_set_tuning", _lib.quasar_set_tuning(waves, wgs_per_cu, depth))
-
-
-def sequence_set_form(form: int) -> None:
-    """0: sequences choose their kernel form when prepared; 1: always the form without specialised waves."""
-    _check("quasar_sequence_set_form", _lib.quasar_sequence_set_form(form))
 
 
 def packed_bytes(N: int, K: int) -> int:
@@ -743,11 +737,6 @@ class Sequence:
     def n_flag_waits(self) -> int:
         """Phases gated by the completion flags of their producer phases (write-once buffers)."""
         return self.handle.words[13]
-
-    @property
-    def specialised_waves(self) -> bool:
-        """True when the step runs as the kernel form with compute, staging and reducing waves."""
-        return bool(self.handle.words[14])
 
     def run(self) -> None:
         _check("quasar_sequence_run",

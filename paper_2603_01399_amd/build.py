@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libquasar.so")
 SOURCES = ["quasar_api.hip"]
-HEADERS = ["quasar_device.hpp", "stream_gemm.hpp", "stream_sequence.hpp", "stream_step.hpp", "stream_w8a8.hpp", "stream_w4.hpp", "drafter.hpp", "attention.hpp", "sample.hpp", "pack.hpp", "probe.hpp"]
+HEADERS = ["quasar_device.hpp", "stream_gemm.hpp", "stream_sequence.hpp", "stream_w8a8.hpp", "stream_w4.hpp", "drafter.hpp", "attention.hpp", "sample.hpp", "pack.hpp", "probe.hpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

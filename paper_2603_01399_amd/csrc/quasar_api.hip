@@ -16,7 +16,6 @@
 #include "probe.hpp"
 #include "stream_gemm.hpp"
 #include "stream_sequence.hpp"
-#include "stream_step.hpp"
 #include "sample.hpp"
 #include "stream_w8a8.hpp"
 #include "stream_w4.hpp"
@@ -29,7 +28,7 @@ namespace {
 
 constexpr int kMaxLds = 160 * 1024;          // gfx950 LDS per compute unit
 constexpr int kSingleChunkX = 128 * 1024;    // activation bytes allowed when K needs no chunking
-constexpr int kMultiChunkX = 64 * 1024;      // activation bytes per chunk otherwise (leaves the whole-step kernel room for its weight queues)
+constexpr int kMultiChunkX = 96 * 1024;      // activation bytes per chunk otherwise
 constexpr int kMinLds = 82 * 1024;           // > half the LDS: at most one workgroup per compute unit
 constexpr int kMaxGrid = 4096;               // bound on workgroups (sizes the argmax partials)
 
@@ -473,16 +472,14 @@ constexpr int kSeqWaves = 16;
 #endif
 constexpr int kSeqDepth = QUASAR_SEQ_DEPTH;
 constexpr int kSeqMagic = 0x51534551;   // "QSEQ"
-constexpr unsigned int kSeqSpinLimit = 4000000u;
-constexpr unsigned int kStepWaitTicks = 2000000u;   // 20 ms of the 100 MHz clock: bound on any wait of stream_step_kernel
-std::atomic<int> g_seq_form{0};                     // 0: choose, 1: always stream_sequence_kernel
+// Bound on any single wait inside the whole-step launch: 200 ms of the 100 MHz constant clock.  A step takes
+// about 2 ms; a wait that long means a workgroup is not running at all, and the launch then ends with the
+// error word set instead of holding the device.
+constexpr unsigned int kSeqSpinLimit = 20000000u;
 
 struct SeqHandle {   // lives in quasar_sequence::words
     int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears, a8;
     int n_barriers, n_flag_waits;
-    int split;           // 1: stream_step_kernel (specialised waves), 0: stream_sequence_kernel
-    int split_lds_bytes;
-    int acc_bytes, queue_steps;
 };
 static_assert(sizeof(SeqHandle) <= sizeof(quasar_sequence), "handle must fit");
 
@@ -659,21 +656,6 @@ int launch_sequence(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
     // Plain launch: one workgroup per compute unit is resident by construction (grid = number
     // of compute units, one workgroup fits each); a cooperative launch would add ~20 us.
     hipLaunchKernelGGL(kernel, dim3(h.grid), dim3(kSeqWaves * 64), (unsigned int)h.lds_bytes, st, sp);
-    return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
-}
-
-// Ring depth of the compute waves: 11 waves per compute unit leave each up to 168 registers.
-#ifndef STEP_DEPTH
-#define STEP_DEPTH 24
-#endif
-template <int MP> constexpr int step_depth() { return MP == 32 ? 16 : STEP_DEPTH; }
-
-template <int MP, bool W16>
-int launch_step(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
-    auto kernel = stream_step_kernel<MP, W16, step_depth<MP>()>;
-    if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return QUASAR_ERR_HIP;
-    hipLaunchKernelGGL(sequence_reset_kernel, dim3(1), dim3(64), 0, st, sp.sync);
-    hipLaunchKernelGGL(kernel, dim3(h.grid), dim3(kStepWaves * 64), (unsigned int)h.split_lds_bytes, st, sp);
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
@@ -859,59 +841,6 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     }
     const int lds = xs_max + sc_max + 2 * kSeqWaves * NB * 1024 + acc_max;
     if (lds > kMaxLds) return QUASAR_ERR_SHAPE;
-
-    // ---- the form with specialised waves (stream_step_kernel): bf16 activations, no phase that needs
-    // the device-wide barrier, every flag-gated input a plain column range of at most two earlier
-    // output segments, per-tile flags within the workspace
-    const int split_fixed = xs_max + kStepCtrlBytes + kStepNR * kStepNV * (MP == 8 ? 512 : NB * 1024) + acc_max;
-    // weight queue per compute wave: a power of two steps, from what the LDS has left
-    int queue_steps = kStepMaxQueue;
-    while (queue_steps >= 2 && split_fixed + queue_steps * kStepNC * 1024 > kMaxLds) queue_steps /= 2;
-    const int split_lds = split_fixed + queue_steps * kStepNC * 1024;
-    bool split = !a8 && g_seq_form.load() == 0 && queue_steps >= 2;
-    {
-        const long long flag_cap = (long long)(n_linears + 1) * kMaxGrid;
-        long long nflags = 0;
-        for (SeqPhase &p : phases) {
-            if (p.wait == SEQ_WAIT_BARRIER) split = false;
-            p.flag_off = (int)nflags;
-            nflags += p.kind == EPI_ARGMAX ? G : (p.publish ? p.T : 0);
-            if (nflags > flag_cap || nflags >= (1ll << 30)) { split = false; break; }
-        }
-        const int KSTEP = w16 ? kStepK16 : kStepK8;
-        for (size_t pi = 0; split && pi < phases.size(); ++pi) {
-            SeqPhase &p = phases[pi];
-            p.src[0] = p.src[1] = SeqPhase::Src{0, 0, 0, 0};
-            p.fine = 0;
-            if (p.wait != SEQ_WAIT_FLAGS) continue;
-            const uintptr_t xa = reinterpret_cast<uintptr_t>(p.x);
-            const Range xr{xa, reinterpret_cast<uintptr_t>(p.x + (M - 1) * p.ldx + p.K)};
-            int ns = 0;
-            for (const Out &o : outs) {
-                if (!overlaps(xr, o.r)) continue;
-                if ((int)pi <= o.ph || ns == 2 || o.ldy != p.ldx) { split = false; break; }
-                // column k of x is column k - delta of the segment
-                const long long delta = ((long long)reinterpret_cast<uintptr_t>(o.y) - (long long)xa) / 2;
-                if (delta <= -(long long)p.ldx || delta >= (long long)p.ldx) { split = false; break; }
-                const long long k_lo = delta > 0 ? delta : 0;
-                const long long k_hi = delta + o.N < p.K ? delta + o.N : p.K;
-                if (k_hi <= k_lo || (k_lo - delta) % kTileRows) { split = false; break; }
-                const SeqPhase &pp = phases[o.ph];
-                p.src[ns].k_lo = (int)k_lo;
-                p.src[ns].k_hi = (int)k_hi;
-                p.src[ns].flag0 = pp.flag_off + pp.seg[o.seg].tile_begin + (int)((k_lo - delta) / kTileRows);
-                ++ns;
-            }
-            if (!split) break;
-            if (ns == 0) { split = false; break; }
-            // a compute wave's K slice may be fetched as soon as its own producer tiles are done if no
-            // 128-byte line of x holds columns of another slice's producers: rows on line boundaries
-            // (slices are cut at multiples of 32 or 64 columns; the kernel widens them to whole lines),
-            // and at most 64 flags per slice and source
-            const int slice_cols = ((p.SC * kStepVPW + kStepNV - 1) / kStepNV + 1) * KSTEP + 126;
-            p.fine = (xa % 128 == 0 && (p.ldx * 2) % 128 == 0 && slice_cols / kTileRows + 1 <= 64) ? 1 : 0;
-        }
-    }
     if (hipMemcpy(plan_device, phases.data(), phases.size() * sizeof(SeqPhase), hipMemcpyHostToDevice) != hipSuccess)
         return QUASAR_ERR_HIP;
     if (hipMemset(static_cast<unsigned char *>(plan_device) + (size_t)(n_linears + 1) * sizeof(SeqPhase), 0,
@@ -925,22 +854,29 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     h.xs_bytes = xs_max; h.sc_bytes = sc_max; h.lds_bytes = lds < kMinLds ? kMinLds : lds; h.grid = G;
     h.has_verify = verify ? 1 : 0; h.n_linears = (int)n_linears; h.a8 = a8 ? 1 : 0;
     h.n_barriers = 0; h.n_flag_waits = 0;
-    h.split = split ? 1 : 0;
-    h.split_lds_bytes = split_lds < kMinLds ? kMinLds : split_lds;
-    h.acc_bytes = acc_max;
-    h.queue_steps = queue_steps;
     for (const SeqPhase &p : phases) {
         if (p.wait == SEQ_WAIT_BARRIER) ++h.n_barriers;
         if (p.wait == SEQ_WAIT_FLAGS) ++h.n_flag_waits;
     }
+    // The launch relies on every workgroup being resident at once (they wait for each other): one
+    // workgroup of this shape must fit a compute unit, and the grid is one workgroup per compute unit.
+    {
+        int per_cu = 0;
+        hipError_t e = hipSuccess;
+        const size_t lds_dyn = (size_t)h.lds_bytes;
+#define QUASAR_OCC(MPV, W16V, A8V)                                                                                   \
+        (allow_large_lds(reinterpret_cast<const void *>(stream_sequence_kernel<MPV, W16V, A8V, kSeqWaves, kSeqDepth>)) \
+             ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, stream_sequence_kernel<MPV, W16V, A8V, kSeqWaves, kSeqDepth>, \
+                                                            kSeqWaves * 64, lds_dyn)                                  \
+             : hipErrorUnknown)
+        if (w16) e = MP == 8 ? QUASAR_OCC(8, true, false) : (MP == 16 ? QUASAR_OCC(16, true, false) : QUASAR_OCC(32, true, false));
+        else if (a8) e = MP == 8 ? QUASAR_OCC(8, false, true) : (MP == 16 ? QUASAR_OCC(16, false, true) : QUASAR_OCC(32, false, true));
+        else e = MP == 8 ? QUASAR_OCC(8, false, false) : (MP == 16 ? QUASAR_OCC(16, false, false) : QUASAR_OCC(32, false, false));
+#undef QUASAR_OCC
+        if (e != hipSuccess || per_cu < 1) return QUASAR_ERR_HIP;
+    }
     std::memset(seq, 0, sizeof(*seq));
     std::memcpy(seq, &h, sizeof(h));
-    return QUASAR_OK;
-}
-
-int quasar_sequence_set_form(int form) {
-    if (form != 0 && form != 1) return QUASAR_ERR_SHAPE;
-    g_seq_form = form;
     return QUASAR_OK;
 }
 
@@ -978,22 +914,6 @@ int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, voi
     sp.zeros = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(plan_device) +
                                                (size_t)(h.n_linears + 1) * sizeof(SeqPhase));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (h.split) {
-        sp.spin_limit = kStepWaitTicks;
-        sp.acc_bytes = h.acc_bytes;
-        sp.queue_steps = h.queue_steps;
-#ifdef STEP_STATS
-        sp.stats = sp.partial + 65536;
-#endif
-        if (h.w16) {
-            if (h.MP == 8) return launch_step<8, true>(h, sp, st);
-            if (h.MP == 16) return launch_step<16, true>(h, sp, st);
-            return launch_step<32, true>(h, sp, st);
-        }
-        if (h.MP == 8) return launch_step<8, false>(h, sp, st);
-        if (h.MP == 16) return launch_step<16, false>(h, sp, st);
-        return launch_step<32, false>(h, sp, st);
-    }
     if (h.w16) {
         if (h.MP == 8) return launch_sequence<8, true, false>(h, sp, st);
         if (h.MP == 16) return launch_sequence<16, true, false>(h, sp, st);

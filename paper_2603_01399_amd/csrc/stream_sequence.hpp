@@ -58,13 +58,9 @@ struct SeqPhase {
     int V;
     int producer[2];         // SEQ_WAIT_FLAGS: phases whose completion flags gate this input (-1: unused)
     int publish;             // a later phase waits for this phase's flags
-    int flag_off;            // stream_step_kernel: this phase's per-tile flags start here (vocabulary phase: per workgroup)
+    int pad_;
     const float *smooth;     // W8A8: per-channel smoothing factors of the input ([K], nullptr: none)
-    // stream_step_kernel, SEQ_WAIT_FLAGS: columns [k_lo, k_hi) of x are rows of an earlier phase's
-    // output segment; the tile that wrote column k raised flag flag0 + (k - k_lo) / 16
-    struct Src { int k_lo, k_hi, flag0, pad; } src[2];
-    int fine;                // rows of x start on 128-byte lines: a K slice may be fetched as soon as its own producers are done
-    int pad_[3];
+    long long pad2_;
 };
 
 typedef const __attribute__((address_space(4))) SeqPhase *const_phase_ptr;   // scalar (constant) loads
@@ -85,11 +81,8 @@ struct SeqParams {
     unsigned int *sync;      // [0] arrival counter, [1] error flag (both zero at launch), [2] launch epoch
     unsigned int *flags;     // [nphases][gridDim.x]: epoch of the launch in which the workgroup finished the phase
     unsigned long long *partial;   // argmax phase: [gridDim.x][MP] packed (logit, index) keys
-    unsigned int spin_limit; // bound on polling iterations
+    unsigned int spin_limit; // bound on the time one wait may take, in ticks of the 100 MHz constant clock
     const u32x4 *zeros;      // 1 KB of zeros, never written: what a slot without a weight step loads
-    unsigned long long *stats;   // development builds of stream_step_kernel: per-wave wait totals (nullptr: none)
-    int acc_bytes;           // stream_step_kernel: LDS bytes of the running tile sums (phases with K chunks)
-    int queue_steps;         // stream_step_kernel: weight steps per compute wave's LDS queue
 };
 
 // Data that crosses from one phase to a later one inside the launch (outputs read as the
@@ -111,17 +104,18 @@ __device__ __forceinline__ u32x4 coherent_load_u32x4(const void *p) {
 }
 // All workgroups of the launch meet.  Every wave first waits until its own (coherent) stores
 // have been acknowledged, so whatever the workgroup wrote is readable device-wide once the
-// arrival counter has been bumped.  Polling is bounded: on timeout the error flag is raised
-// and every later wait falls through, so the grid always drains.
+// arrival counter has been bumped.  Polling is bounded in TIME (spin_limit ticks of the 100 MHz
+// constant clock, measured per wait): on expiry the error flag is raised and every later wait falls
+// through, so the grid always drains and a stall cannot last longer than that, whatever a poll costs.
 __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int target, unsigned int spin_limit) {
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     lds_barrier();
     if (threadIdx.x == 0) {
         __hip_atomic_fetch_add(as_global(&sync[0]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        unsigned int n = 0;
+        const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();   // 100 MHz, the same on every compute unit
         while (__hip_atomic_load(as_global(&sync[0]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
             if (__hip_atomic_load(as_global(&sync[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
-            if (++n > spin_limit) {
+            if (__builtin_amdgcn_s_memrealtime() - t0 > spin_limit) {
                 __hip_atomic_store(as_global(&sync[1]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
@@ -131,35 +125,10 @@ __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int ta
     lds_barrier();
 }
 
-#ifdef QUASAR_SEQ_TRACE
-// development aid: workgroups 0 and 100 record the shader clock at a few points of every phase
-#define QUASAR_TRACE(slot)                                                                          \
-    if ((b == 0 || b == 100) && tid == 0 && c_ph < 400)                                              \
-        reinterpret_cast<unsigned long long *>(sp.partial)[65536 + ((b ? 1 : 0) * 400 + c_ph) * 8 + (slot)] = \
-            __builtin_readcyclecounter();                                                           \
-    if (tid == 0 && c_ph < 60 && b < 256 && ((slot) == 0 || (slot) == 4 || (slot) == 5))            \
-        reinterpret_cast<unsigned long long *>(sp.partial)[84000 + (c_ph * 256 + b) * 3 + ((slot) == 0 ? 0 : (slot) - 3)] = \
-            (__builtin_amdgcn_s_memrealtime() & 0x0000FFFFFFFFFFFFull) |                            \
-            ((unsigned long long)__builtin_amdgcn_s_getreg(6164) << 60) |                           \
-            ((unsigned long long)(__builtin_amdgcn_s_getreg(63492) & 0xFFFF) << 44);
-#define QUASAR_TRACE_SLOT(tag)                                                                      \
-    if (b == 0 && tid == 64 && trace_n < 2000) {                                                     \
-        reinterpret_cast<unsigned long long *>(sp.partial)[80000 + trace_n] =                       \
-            ((unsigned long long)(tag) << 56) | (__builtin_readcyclecounter() & 0x00FFFFFFFFFFFFFFull); \
-        ++trace_n;                                                                                  \
-    }
-#else
-#define QUASAR_TRACE(slot)
-#define QUASAR_TRACE_SLOT(tag)
-#endif
-
-#ifndef QUASAR_SEQ_XB
-#define QUASAR_SEQ_XB 8
-#endif
-// Ring slots are refilled in groups of this many, after the group's last slot has been used.
-#ifndef QUASAR_SEQ_GR
-#define QUASAR_SEQ_GR 4
-#endif
+// Activation pieces a thread holds per staging batch; ring slots are refilled in groups of kSeqRefillGroup,
+// after the group's last slot has been used.
+constexpr int kSeqStageBatch = 8;
+constexpr int kSeqRefillGroup = 4;
 
 // A8 selects the W8A8 form of the linears: the activations are smoothed and quantised per
 // token while they are staged (same arithmetic as stream_w8a8.hpp), the weight step goes
@@ -172,8 +141,8 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     constexpr int PPS = (W16 || A8) ? 4 : 8;   // 16-byte LDS pieces per step and token
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
     constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
-    constexpr int XB = QUASAR_SEQ_XB;
-    constexpr int GR = QUASAR_SEQ_GR;
+    constexpr int XB = kSeqStageBatch;
+    constexpr int GR = kSeqRefillGroup;
     static_assert(GR >= 1 && (GR & (GR - 1)) == 0 && D % GR == 0, "refill groups tile the ring");
     constexpr int nthreads = NW * 64;
     static_assert(NW == 16, "the in-kernel second stage of the verify phase assumes 1024 threads");
@@ -441,8 +410,8 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     auto flags_wait = [&](int pp) {
         if (w != 0) return;
         const unsigned int *row = sp.flags + (long long)pp * G;
+        const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
         for (int t0 = 4 * lane; t0 < G; t0 += 256) {
-            unsigned int spins = 0;
             for (;;) {
                 unsigned int f[4];
 #pragma unroll
@@ -451,7 +420,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                                                           __HIP_MEMORY_SCOPE_AGENT)
                                       : epoch;
                 if (f[0] == epoch && f[1] == epoch && f[2] == epoch && f[3] == epoch) break;
-                if (++spins > sp.spin_limit ||
+                if (__builtin_amdgcn_s_memrealtime() - t_begin > sp.spin_limit ||
                     __hip_atomic_load(as_global(&sp.sync[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
                     __hip_atomic_store(as_global(&sp.sync[1]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     break;
@@ -567,7 +536,6 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             if (c_ph >= nph) return false;
             const auto &P = phases[c_ph];
             if (c_c == 0) {
-                QUASAR_TRACE(0)
                 c_C = P.C;
                 c_kind = P.kind;
                 c_t0 = (int)(((unsigned int)P.T * (unsigned int)b) / (unsigned int)G);
@@ -602,15 +570,11 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             unit_left = (c_ntiles * c_nsl + GR - 1) & ~(GR - 1);
             nocomp = false;
             c_reseg();
-            QUASAR_TRACE(1)
             if constexpr (A8) x_quant(P, c_c, P.wait == SEQ_WAIT_BARRIER);
             else x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
-            QUASAR_TRACE(2)
             // known-empty load queue: keeps the counted waits of the ring exact (see stream_gemm.hpp)
             __builtin_amdgcn_s_waitcnt(0x0F70);
-            QUASAR_TRACE(3)
             lds_barrier();
-            QUASAR_TRACE(4)
             return true;
         }
     };
@@ -621,9 +585,6 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     // makes the compiler lose count of the outstanding ring loads and drain the ring.  When the
     // sequence ends in the middle of a round the rest of the round runs without arithmetic and the
     // loop is left at its top.
-#ifdef QUASAR_SEQ_TRACE
-    int trace_n = 0;
-#endif
     const unsigned char *xsb = lds;
     bool done = false;
     c_leave();
@@ -642,7 +603,6 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 if (d == 0 && done) break;
                 unit_left -= GR;
             }
-            QUASAR_TRACE_SLOT(1)
             const u32x4 wv = ring[d];
             const unsigned char *xp = xsb + (xlane + c_xoff);
             [[maybe_unused]] const unsigned long long la = l_base;
@@ -678,7 +638,6 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 l_base += l_inc;
                 if (__builtin_expect(--l_left == 0, 0)) l_event();
             }
-            QUASAR_TRACE_SLOT(4)
             if (!nocomp && __builtin_expect(--c_left == 0, 0)) {
                 // ---- tile end: cross-wave sum through LDS, fixed order (W8A8: exact integers)
                 using acc_t = std::conditional_t<A8, i32x4, f32x4>;
@@ -693,9 +652,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                         acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
                     }
                 }
-                QUASAR_TRACE_SLOT(6)
                 lds_barrier();
-                QUASAR_TRACE_SLOT(7)
                 // the epilogue rotates over waves 1..NW-1: wave 0 polls for the next phase's input
                 // and should never have to wait for its own stores
                 if (w == 1 + (c_tl % (NW - 1))) {
@@ -712,7 +669,6 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                             if (c_c < c_C - 1) *a = rsum[nb];
                         }
                     }
-                    QUASAR_TRACE_SLOT(8)
                     if (c_c == c_C - 1) {
                         const int n0 = (c_t0 + c_tl - c_tb) * kTileRows + 4 * g;
                         float s4[4] = {1.f, 1.f, 1.f, 1.f};
@@ -758,11 +714,9 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     }
                 }
                 parity ^= 1;
-                QUASAR_TRACE_SLOT(5)
                 // advance the compute front; after the unit's last tile only padding is left
                 if (++c_tl >= c_ntiles) {
                     nocomp = true;
-                    QUASAR_TRACE(5)
                     c_leave();
                 } else {
                     if (__builtin_expect(c_t0 + c_tl == c_seg_end, 0)) c_reseg();

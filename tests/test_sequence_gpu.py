@@ -127,7 +127,6 @@ def test_sequence_chain_vs_oracle_and_single_calls(qb, M, hidden, kv, inter, bf1
     assert seq.nphases == 4 * n_layers + 1          # q|k|v, o, gate|up, down per layer + the head
     # every buffer is written once: all dependent phases wait for their data, none at a barrier
     assert seq.n_barriers == 0 and seq.n_flag_waits == 4 * n_layers
-    assert seq.specialised_waves                    # write-once buffers: the form with compute, staging and reducing waves
     seq.run()
     torch.cuda.synchronize()
     assert not seq.timed_out()
@@ -172,44 +171,9 @@ def test_sequence_chain_vs_oracle_and_single_calls(qb, M, hidden, kv, inter, bf1
         assert torch.equal(first[li].view(torch.int16), bufs[li]["down"].view(torch.int16))
 
 
-@pytest.mark.parametrize("M,hidden,kv,inter,bf16", [(8, 512, 128, 8320, False), (16, 256, 64, 768, True)])
-def test_sequence_both_kernel_forms_give_the_same_bits(qb, M, hidden, kv, inter, bf16):
-    """The form with specialised waves and the form in which every wave streams and synchronises cut
-    K into the same 16 slices and sum them in the same order."""
-    print("sequence forms", M, hidden, kv, inter, bf16, flush=True)
-    n_layers, V = 2, 4096
-    layers = build_model(qb, n_layers, hidden, kv, inter, seed=9300 + M, bf16=bf16)
-    x0 = synth.activations_bf16(M, hidden, seed=9310 + M)
-    wv = synth.normal_weights(V, hidden, seed=9320 + M, std=1.0 / np.sqrt(hidden))
-    if bf16:
-        hp, hs = qb.pack_bf16_weights(f32_to_dev(wv)), None
-    else:
-        hp, hs = qb.quantize_weights(f32_to_dev(wv))
-    draft = i32_to_dev(np.arange(1, M, dtype=np.int32))
-    res = []
-    try:
-        for form in (0, 1):
-            qb.sequence_set_form(form)
-            bufs, h_dev = gpu_buffers(layers, M, x0)
-            am = torch.full((M,), -1, dtype=torch.int32, device="cuda")
-            acc = torch.full((1,), -1, dtype=torch.int32, device="cuda")
-            seq = qb.Sequence(linear_list(layers, bufs), verify=(h_dev, hp, hs, V, draft, am, acc))
-            assert seq.specialised_waves == (form == 0)
-            seq.run()
-            torch.cuda.synchronize()
-            assert not seq.timed_out()
-            res.append((bufs, am, acc))
-    finally:
-        qb.sequence_set_form(0)
-    for li in range(n_layers):
-        for name in ("q", "k", "v", "o", "gate", "up", "down"):
-            assert torch.equal(res[0][0][li][name].view(torch.int16), res[1][0][li][name].view(torch.int16)), (li, name)
-    assert torch.equal(res[0][1], res[1][1]) and torch.equal(res[0][2], res[1][2])
-
-
 def test_sequence_rows_off_cache_line_boundaries(qb):
-    """Activation rows that do not start on 128-byte lines (row stride 264 elements): a consumer may then
-    fetch a line only when every producer tile is done; results equal the single calls bit for bit."""
+    """Activation rows that do not start on 128-byte lines (row stride 264 elements), chained through the
+    whole-step launch: results equal the single calls bit for bit."""
     print("sequence odd strides", flush=True)
     M, H, L = 8, 256, 4
     ws = []
@@ -226,7 +190,7 @@ def test_sequence_rows_off_cache_line_boundaries(qb):
         return act
     def as_sequence(act):
         seq = qb.Sequence([(act[i], ws[i][0], ws[i][1], H, act[i + 1]) for i in range(L)])
-        assert seq.specialised_waves and seq.n_barriers == 0
+        assert seq.n_barriers == 0
         seq.run()
         torch.cuda.synchronize()
         assert not seq.timed_out()
