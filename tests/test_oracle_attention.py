@@ -116,3 +116,34 @@ def test_attention_is_causal_over_the_new_positions():
     # scaling every query by a positive power of two sharpens the weights but a single visible key
     # still returns its value row
     assert np.array_equal(at.verify_attention(bits(vals(q[:1]) * 8.0), bits(k[:1]), bits(v[:1]))[0, 0], bits(v[:1])[0, 0])
+
+
+def test_attention_two_keys_closed_form_pins_the_score_scale():
+    """Softmax over two scores is the logistic function: with q = a e0, k1 = b e0, k2 = 0 the weights are
+    sigma(a b / sqrt(d)) and its complement.  The bit patterns in tests/golden/attention_two_keys.txt were
+    worked by hand; a score scaled by 1/d (or not at all) gives other bits."""
+    import os
+    fx = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "attention_two_keys.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                fx[k] = v
+    d, a, b = int(fx["d"]), float(fx["a"]), float(fx["b"])
+    q = np.zeros((1, 1, d)); q[0, 0, 0] = a
+    k = np.zeros((2, 1, d)); k[0, 0, 0] = b
+    v = np.zeros((2, 1, d)); v[0, 0, 0] = 1.0; v[1, 0, 1] = 1.0
+    out = at.verify_attention(bits(q), bits(k), bits(v))
+    assert int(out[0, 0, 0]) == int(fx["w1_bf16"], 16)
+    assert int(out[0, 0, 1]) == int(fx["w2_bf16"], 16)
+    assert not out[0, 0, 2:].any()
+    # the same through grouped heads and a longer prefix of zero keys: n zero keys share what w1 leaves
+    n0 = 3
+    k2 = np.zeros((1 + n0, 2, d)); k2[0, :, 0] = b
+    v2 = np.zeros((1 + n0, 2, d)); v2[0, :, 0] = 1.0
+    q2 = np.zeros((1, 4, d)); q2[0, :, 0] = a
+    out2 = vals(at.verify_attention(bits(q2), bits(k2), bits(v2)))
+    w = np.exp(2.0) / (np.exp(2.0) + n0)
+    assert np.all(np.abs(out2[0, :, 0] - w) <= w * 2.0 ** -8)
+    # and the value the wrong scale would give is far from what the oracle returns
+    assert abs(vals(out)[0, 0, 0] - float(fx["w1_if_scaled_by_d"])) > 0.2
