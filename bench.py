@@ -220,6 +220,24 @@ def main() -> int:
     achieved = step_bytes[1] / us_step / 1e3
     avg_b, avg_us = float(step_bytes[1]), us_step
 
+    # what the timed launch left behind against the same step through the single-call entry points
+    # (same buffers, so the launch's results are copied aside first): all bits must agree
+    kept = [{k: v.clone() for k, v in b.items()} for b in bufs]
+    kept_am, kept_acc = out_argmax.clone(), out_accept.clone()
+    out_argmax.fill_(-1)
+    out_accept.fill_(-1)
+    run_step(calls8)
+    torch.cuda.synchronize()
+    for li in range(L):
+        for k in bufs[li]:
+            assert torch.equal(kept[li][k].view(torch.int16), bufs[li][k].view(torch.int16)), \
+                f"timed launch differs from the single calls at layer {li} output {k}"
+    assert torch.equal(kept_am, out_argmax) and torch.equal(kept_acc, out_accept), \
+        "timed launch's argmax / accepted length differ from the single call's"
+    log(f"timed launch verified against the single calls: {7 * L} outputs, argmax and accepted length "
+        f"({int(kept_acc[0])}) bit-identical")
+    del kept
+
     # The same weights with every linear reading a resident input instead of its predecessor's
     # output (no phase waits for another): what the weight stream alone sustains.
     fixed_in = {4096: h0, 12288: torch.randn((M, 12288), generator=gen, device=dev, dtype=torch.float32)
@@ -253,7 +271,8 @@ def main() -> int:
         except Exception:
             traffic = None
 
-    detail = {"independent_inputs_us_per_step": us_free,
+    detail = {"timed_launch_bit_identical_to_single_calls": True,
+              "independent_inputs_us_per_step": us_free,
               "independent_inputs_hbm_gbps": step_bytes[1] / us_free / 1e3,
               "w8a8_us_per_step": us_w8a8, "w8a8_hbm_gbps": step_bytes[1] / us_w8a8 / 1e3}
     us_twin = None

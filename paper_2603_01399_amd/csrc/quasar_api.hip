@@ -704,7 +704,8 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     // every cache line read so far in the launch (never cleared): a line that some compute unit has
     // already fetched may sit in a cache with its old contents, so an input that is written inside the
     // launch AFTER one of its lines was read must be re-read past the caches (barrier form)
-    std::vector<Range> lines_read;
+    struct LineRead { Range r; int ph; };
+    std::vector<LineRead> lines_read;
     auto lines = [](const Range &r) { return Range{r.lo & ~(uintptr_t)127, (r.hi + 127) & ~(uintptr_t)127}; };
     // How does a phase reading `xr` (and writing `yrs`) have to wait?  (see SEQ_WAIT_* in
     // stream_sequence.hpp)  Writes that clash with anything touched since the last barrier, or
@@ -718,10 +719,12 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
             for (const Range &rd : reads) if (overlaps(y, rd)) write_clash = true;
         }
         for (const Range &wr : writes) if (overlaps(xr, wr)) raw = true;
-        bool written = raw;
-        for (const Out &o : outs) if (overlaps(lines(xr), lines(o.r))) written = true;
-        if (written)
-            for (const Range &lr : lines_read) if (overlaps(lines(xr), lr)) write_clash = true;
+        // a line of this input that an earlier phase read no later than the phase that (re)wrote it
+        for (const Out &o : outs) {
+            if (!overlaps(lines(xr), lines(o.r))) continue;
+            for (const LineRead &lr : lines_read)
+                if (lr.ph <= o.ph && overlaps(lines(xr), lr.r) && overlaps(lines(o.r), lr.r)) write_clash = true;
+        }
         if (write_clash) return SEQ_WAIT_BARRIER;
         if (!raw) return SEQ_WAIT_NONE;
         int n = 0;
@@ -789,7 +792,7 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
         p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(xr, {yr}, p.producer);
         if (p.wait == SEQ_WAIT_BARRIER) { reads.clear(); writes.clear(); }
         reads.push_back(xr);
-        lines_read.push_back(lines(xr));
+        lines_read.push_back(LineRead{lines(xr), (int)phases.size()});
         writes.push_back(yr);
         note_output(yr, (int)phases.size(), 0, d.N, d.ldy, d.y);
         phases.push_back(p);

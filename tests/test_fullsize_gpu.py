@@ -161,3 +161,151 @@ def test_w4_qwen3_8b_layer_and_full_vocab(qb):
         d = synth.draft_with_matches(t, jj, V, M - 1)
         am, acc = qb.w4_lmhead_verify(bf16_to_dev(h), wp, V, i32_to_dev(d), ws)
         assert np.array_equal(am.cpu().numpy(), t) and int(acc.cpu()[0]) == jj
+
+
+@pytest.mark.timeout(900)
+def test_whole_step_launch_at_benchmark_size(qb):
+    """The launch the benchmark times: 36 Qwen3-8B-shaped layers (252 linears) and the vocabulary
+    projection with greedy acceptance at V = 151936, M = 8, in ONE persistent launch.
+
+    * every one of the 252 linear outputs, the argmax and the accepted length equal, bit for bit,
+      what the single-call entry points give on the same buffers' contents;
+    * layers 0, 17 and 35 (weights drawn on the host, quantised on both sides, codes and scales
+      compared) are checked against the oracle, each from the bf16 input that layer consumed: an
+      oracle chain through all 144 dependent linears would differ from any bf16 pipeline by the
+      accumulated rounding, far beyond the per-linear bar, so the oracle is applied layer by layer;
+    * the vocabulary weights are drawn on the host with planted winners, so that the oracle's
+      argmax is unambiguous; drafts with j in {0, 3, 7} leading matches give accepted length j;
+    * the W8A8 form of the same launch equals the W8A8 single calls bit for bit, and the oracle
+      exactly (integer arithmetic) on the checked layers.
+    """
+    from oracle import quasar_w8a8_ref as a8
+    M, H, V, L = 8, synth.QWEN3_8B_HIDDEN, synth.QWEN3_VOCAB, synth.QWEN3_8B_LAYERS
+    shapes = synth.QWEN3_8B_LAYER
+    checked = (0, 17, 35)
+    dev = torch.device("cuda")
+    gen = torch.Generator(device=dev)
+    layers, host = [], {}
+    for li in range(L):
+        lin = []
+        for i, (name, K, N) in enumerate(shapes):
+            std = 1.0 / np.sqrt(K)                       # unit gain: the chain stays O(1) through 36 layers
+            if li in checked:
+                w = synth.normal_weights(N, K, seed=synth.seed_for(11, li, i), std=std)
+                q_ref, s_ref = ref.quantize_weights(w)
+                wq, sc = qb.quantize_weights(f32_to_dev(w))
+                assert np.array_equal(bf16_to_host(sc), s_ref), (li, name)
+                assert np.array_equal(qb.unpack_weights(wq, N, K).cpu().numpy(), q_ref), (li, name)
+                host[(li, name)] = (q_ref, s_ref)
+            else:
+                gen.manual_seed(synth.seed_for(11, li, i))
+                w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * std
+                wq, sc = qb.quantize_weights(w)
+            del w
+            lin.append((name, K, N, wq, sc))
+        layers.append(lin)
+        if li % 6 == 5:
+            print("weights of", li + 1, "layers resident", flush=True)
+    x0 = bf16_to_dev(synth.activations_bf16(M, H, seed=synth.seed_for(11, 99, 0)))
+
+    def buffers():
+        return [{n: torch.zeros((M, N), dtype=torch.bfloat16, device=dev) for n, _, N in shapes} for _ in range(L)]
+
+    def linears(bufs):
+        lst = []
+        for li, lin in enumerate(layers):
+            hin = x0 if li == 0 else bufs[li - 1]["down_proj"]
+            b = bufs[li]
+            src = {"q_proj": hin, "k_proj": hin, "v_proj": hin, "o_proj": b["q_proj"], "gate_proj": b["o_proj"],
+                   "up_proj": b["o_proj"], "down_proj": b["gate_proj"]}
+            for name, K, N, wq, sc in lin:
+                lst.append((src[name], wq, sc, N, b[name]))
+        return lst
+
+    # ---- the step as single calls (no split-K workspace): gives the hidden state the head will read
+    ref_bufs = buffers()
+    for x, wq, sc, N, y in linears(ref_bufs):
+        qb.w8_linear(x, wq, sc, N, y)
+    torch.cuda.synchronize()
+    h_last = bf16_to_host(ref_bufs[L - 1]["down_proj"])
+    assert np.isfinite(ref.bf16_bits_to_f64(h_last)).all()
+
+    print("vocabulary weights: drawing, planting, quantising on both sides", flush=True)
+    wv = synth.normal_weights(V, H, seed=synth.seed_for(11, 99, 1))
+    t = synth.distinct_targets(M, V, seed=synth.seed_for(11, 99, 2))
+    synth.plant_targets(wv, h_last, t)
+    qv_ref, sv_ref = ref.quantize_weights(wv)
+    head_q, head_s = qb.quantize_weights(f32_to_dev(wv))
+    del wv
+    assert np.array_equal(bf16_to_host(head_s), sv_ref)
+    assert np.array_equal(qb.unpack_weights(head_q, V, H).cpu().numpy(), qv_ref)
+    print("oracle logits", flush=True)
+    base = ref.lmhead_verify(h_last, qv_ref, sv_ref, np.zeros(0, np.int32))
+    assert np.array_equal(base["argmax"], t)
+    assert np.all(base["top1"] - base["top2"] > TOL * base["maxabs"])
+
+    # ---- ONE persistent launch over the same weights
+    bufs = buffers()
+    draft = torch.zeros(M - 1, dtype=torch.int32, device=dev)
+    out_argmax = torch.full((M,), -1, dtype=torch.int32, device=dev)
+    out_accept = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    seq = qb.Sequence(linears(bufs), verify=(bufs[L - 1]["down_proj"], head_q, head_s, V, draft, out_argmax, out_accept))
+    assert seq.nphases == 4 * L + 1 and seq.n_barriers == 0 and seq.n_flag_waits == 4 * L
+    ws = qb.make_workspace(M, V, H)
+    for j in (0, 3, 7):
+        d = synth.draft_with_matches(t, j, V, M - 1)
+        draft.copy_(i32_to_dev(d))
+        out_argmax.fill_(-1)
+        out_accept.fill_(-1)
+        seq.run()
+        torch.cuda.synchronize()
+        assert not seq.timed_out()
+        assert np.array_equal(out_argmax.cpu().numpy(), t), j
+        assert int(out_accept.cpu()[0]) == j == ref.accepted_length(base["argmax"], d)
+        am2, acc2 = qb.lmhead_verify(ref_bufs[L - 1]["down_proj"], head_q, head_s, V, draft, ws)
+        assert torch.equal(am2, out_argmax) and torch.equal(acc2, out_accept)
+    for li in range(L):
+        for name, _, _ in shapes:
+            assert torch.equal(bufs[li][name].view(torch.int16), ref_bufs[li][name].view(torch.int16)), (li, name)
+    print("252 outputs, argmax and accepted length identical to the single calls", flush=True)
+
+    def layer_inputs(b, li):
+        hin = bf16_to_host(x0 if li == 0 else b[li - 1]["down_proj"])
+        return {"q_proj": hin, "k_proj": hin, "v_proj": hin, "o_proj": bf16_to_host(b[li]["q_proj"]),
+                "gate_proj": bf16_to_host(b[li]["o_proj"]), "up_proj": bf16_to_host(b[li]["o_proj"]),
+                "down_proj": bf16_to_host(b[li]["gate_proj"])}
+
+    for li in checked:
+        xin = layer_inputs(bufs, li)
+        for name, K, N in shapes:
+            q_ref, s_ref = host[(li, name)]
+            err = ref.rel_maxabs_err(ref.bf16_bits_to_f64(bf16_to_host(bufs[li][name])),
+                                     ref.w8_linear(xin[name], q_ref, s_ref))
+            print("layer", li, name, "rel err", err, flush=True)
+            assert err <= TOL and err <= 4e-3
+
+    # ---- the W8A8 form of the same launch
+    bufs8 = buffers()
+    seq8 = qb.Sequence(linears(bufs8), verify=(bufs8[L - 1]["down_proj"], head_q, head_s, V, draft, out_argmax, out_accept),
+                       w8a8=True)
+    out_argmax.fill_(-1)
+    out_accept.fill_(-1)
+    seq8.run()
+    torch.cuda.synchronize()
+    assert not seq8.timed_out()
+    ref8 = buffers()
+    for x, wq, sc, N, y in linears(ref8):
+        qb.w8a8_linear(x, wq, sc, N, y=y)
+    am8, acc8 = qb.w8a8_lmhead_verify(ref8[L - 1]["down_proj"], head_q, head_s, V, draft, ws)
+    torch.cuda.synchronize()
+    for li in range(L):
+        for name, _, _ in shapes:
+            assert torch.equal(bufs8[li][name].view(torch.int16), ref8[li][name].view(torch.int16)), (li, name)
+    assert torch.equal(am8, out_argmax) and torch.equal(acc8, out_accept)
+    assert np.array_equal(out_argmax.cpu().numpy(), t)             # the planted margins dwarf the int8 activation error
+    for li in checked:
+        xin = layer_inputs(bufs8, li)
+        for name, K, N in shapes:
+            q_ref, s_ref = host[(li, name)]
+            assert np.array_equal(bf16_to_host(bufs8[li][name]), a8.w8a8_linear(xin[name], q_ref, s_ref)), (li, name)
+    print("W8A8 form identical to its single calls and to the oracle on the checked layers", flush=True)
