@@ -141,6 +141,24 @@ int quasar_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t l
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * quasar_lmhead_verify for callers that cannot allocate or carry a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as quasar_lmhead_verify, without the workspace pair: the per-workgroup
+ * argmax partials live in a 1 MiB array that is part of the library's device image (4096
+ * workgroups x 32 positions x 8 bytes, which covers every shape quasar_lmhead_verify
+ * accepts: M <= 32 and at most 4096 workgroups; anything beyond that is refused with
+ * QUASAR_ERR_SHAPE before any launch).  The call allocates and frees nothing.  Each GPU
+ * holds one copy of the array until the process ends, and every call on that GPU uses it:
+ * calls that overlap on one GPU (different streams, different threads) race on it and must
+ * be serialised by the caller.  Nothing in it needs clearing between calls: each launch
+ * writes every slot that it later reads.
+ */
+int quasar_lmhead_verify_static(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh,
+                                const int8_t *wq_packed, const uint16_t *scales_bf16, int64_t V,
+                                const int32_t *draft_ids, int64_t n_draft,
+                                int32_t *out_argmax, int32_t *out_accept_len, void *hip_stream);
+
+/*
  * Full-precision comparison point (Sec. 3.4 Eq. 11: two bytes per parameter):
  * the same kernels streaming bf16 weights.  quasar_pack_bf16_weights converts
  * (fp32 -> bf16 round-to-nearest-even, or copies bf16) into the tile order.

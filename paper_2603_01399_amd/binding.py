@@ -21,7 +21,7 @@ PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 # every symbol declared in include/quasar.h
 EXPORTS = (
     "quasar_status_string", "quasar_version", "quasar_set_path", "quasar_get_path",
-    "quasar_set_tuning", "quasar_set_tuning_w4",
+    "quasar_set_tuning", "quasar_set_tuning_w4", "quasar_lmhead_verify_static",
     "quasar_packed_bytes", "quasar_packed_bytes_bf16", "quasar_workspace_bytes",
     "quasar_quantize_weights", "quasar_unpack_weights", "quasar_w8_linear", "quasar_lmhead_verify",
     "quasar_pack_bf16_weights", "quasar_bf16_linear", "quasar_bf16_lmhead_verify",
@@ -88,6 +88,7 @@ def _load() -> ctypes.CDLL:
     lib.quasar_unpack_weights.argtypes = [vp, i64, i64, vp, vp]
     lib.quasar_w8_linear.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, vp, sz, vp]
     lib.quasar_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, vp, vp, vp, sz, vp]
+    lib.quasar_lmhead_verify_static.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, i64, vp, vp, vp]
     lib.quasar_pack_bf16_weights.argtypes = [vp, ci, i64, i64, i64, vp, vp]
     lib.quasar_bf16_linear.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, sz, vp]
     lib.quasar_bf16_lmhead_verify.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, sz, vp]
@@ -592,6 +593,27 @@ def lmhead_verify(hidden: torch.Tensor, wq_packed: torch.Tensor, scales: torch.T
                                      _ptr(draft_ids) if n_draft else None, n_draft, _ptr(out_argmax),
                                      _ptr(out_accept), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream()))
+    return out_argmax, out_accept
+
+
+def lmhead_verify_static(hidden: torch.Tensor, wq_packed: torch.Tensor, scales: torch.Tensor, V: int,
+                         draft_ids: torch.Tensor, out_argmax: torch.Tensor, out_accept: torch.Tensor):
+    """quasar_lmhead_verify_static: no workspace, and the outputs are the caller's (nothing is allocated)."""
+    _dev(hidden, "hidden", torch.bfloat16)
+    _dev(wq_packed, "wq_packed", torch.int8)
+    _dev(scales, "scales", torch.bfloat16)
+    _dev(out_argmax, "out_argmax", torch.int32)
+    _dev(out_accept, "out_accept", torch.int32)
+    M, K = hidden.shape
+    n_draft = 0 if draft_ids is None else draft_ids.numel()
+    if n_draft:
+        _dev(draft_ids, "draft_ids", torch.int32)
+    if out_argmax.numel() < M or out_accept.numel() < 1:
+        raise ValueError("out_argmax needs M elements and out_accept one")
+    _check("quasar_lmhead_verify_static",
+           _lib.quasar_lmhead_verify_static(_ptr(hidden), M, K, hidden.stride(0), _ptr(wq_packed), _ptr(scales), V,
+                                            _ptr(draft_ids) if n_draft else None, n_draft, _ptr(out_argmax),
+                                            _ptr(out_accept), _stream()))
     return out_argmax, out_accept
 
 

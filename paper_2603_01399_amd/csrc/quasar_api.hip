@@ -292,6 +292,30 @@ int verify_impl(const uint16_t *h, int64_t M, int64_t K, int64_t ldh, const void
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
 }
 
+// Argmax partials of quasar_lmhead_verify_static: part of the device image, one copy per GPU.
+constexpr size_t kStaticPartialWords = (size_t)kMaxGrid * 32u;
+static __device__ __align__(256) unsigned long long g_verify_scratch[kStaticPartialWords];
+
+// Device address of g_verify_scratch on the current device (looked up once per device; the
+// array's name is only a host-side handle and must never be passed to a kernel).
+int static_scratch(unsigned long long **out) {
+    static std::atomic<unsigned long long *> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return QUASAR_ERR_HIP;
+    unsigned long long *ptr = cached[dev].load();
+    if (!ptr) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(g_verify_scratch)) != hipSuccess || !sym) {
+            (void)hipGetLastError();
+            return QUASAR_ERR_HIP;
+        }
+        ptr = static_cast<unsigned long long *>(sym);
+        cached[dev] = ptr;
+    }
+    *out = ptr;
+    return QUASAR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -397,6 +421,18 @@ int quasar_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int64_t l
                          void *hip_stream) {
     return verify_impl<false>(hidden, M, K, ldh, wq_packed, scales_bf16, V, draft_ids, n_draft, out_argmax,
                               out_accept_len, workspace, workspace_bytes, hip_stream);
+}
+
+int quasar_lmhead_verify_static(const uint16_t *hidden, int64_t M, int64_t K, int64_t ldh, const int8_t *wq_packed,
+                                const uint16_t *scales_bf16, int64_t V, const int32_t *draft_ids, int64_t n_draft,
+                                int32_t *out_argmax, int32_t *out_accept_len, void *hip_stream) {
+    if (const int e = check_mnk(M, V, K)) return e;                  // M <= 32: 32 slots per workgroup suffice
+    unsigned long long *scratch = nullptr;
+    if (const int e = static_scratch(&scratch)) return e;
+    // verify_impl refuses launches of more than kMaxGrid workgroups before anything runs, which
+    // is what the array is sized for
+    return verify_impl<false>(hidden, M, K, ldh, wq_packed, scales_bf16, V, draft_ids, n_draft, out_argmax,
+                              out_accept_len, scratch, kStaticPartialWords * sizeof(unsigned long long), hip_stream);
 }
 
 int quasar_pack_bf16_weights(const void *w, int w_dtype, int64_t N, int64_t K, int64_t ldw, uint16_t *w_packed,
