@@ -71,10 +71,17 @@ int quasar_get_path(void);
  *                          load-ring depth (4 or 8) of the single-call int8 / bf16 kernels; the
  *                          first two can also be preset through the environment variables
  *                          QUASAR_TUNE_NW and QUASAR_TUNE_WGS, read when the library is loaded;
- *   quasar_set_tuning_w4   waves per workgroup and ring depth of the 4-bit kernel.
+ *   quasar_set_tuning_w4   waves per workgroup and ring depth of the 4-bit kernel;
+ *   quasar_set_sequence_form   workgroups per compute unit of the whole-step launch for sequences
+ *                          prepared afterwards: 0 lets quasar_sequence_prepare choose (two alternating
+ *                          workgroups of 8 waves when at most a quarter of the phases wait for an
+ *                          earlier one, M <= 8 and the shapes fit half the LDS; else one of 16 waves),
+ *                          1 or 2 asks for that form (2 makes prepare fail with QUASAR_ERR_SHAPE
+ *                          where it does not fit).  Results are the same bits in both forms.
  * Each returns QUASAR_ERR_SHAPE for a value outside the stated set. */
 int quasar_set_tuning(int waves, int wgs_per_cu, int depth);
 int quasar_set_tuning_w4(int waves, int depth);
+int quasar_set_sequence_form(int workgroups_per_cu);
 
 /* Bytes of the packed int8 / packed bf16 weight buffer for an [N, K] matrix.
  * Int8: exactly one byte per parameter (the 2x footprint reduction of Sec. 3.3,
@@ -180,7 +187,9 @@ int quasar_bf16_lmhead_verify(const uint16_t *hidden, int64_t M, int64_t K, int6
  * vocabulary projection + acceptance) run as ONE persistent launch, so that the weight
  * stream of Sec. 3.4 (Eq. 12: one byte per parameter over the whole model) is not interrupted
  * at every layer boundary.  Results are bit-identical to calling quasar_w8_linear /
- * quasar_lmhead_verify one by one in list order.
+ * quasar_lmhead_verify one by one in list order with no workspace given to quasar_w8_linear
+ * (a workspace lets it split K across workgroups, which sums in another order) and the
+ * single-call kernels in their default shape (16 waves per workgroup).
  *
  * Linears are described on the HOST; consecutive entries that read the same x (q|k|v, gate|up)
  * are executed together.  An entry whose input is the output of earlier entries waits for
@@ -231,6 +240,22 @@ int quasar_sequence_prepare(const quasar_linear_desc *linears, int64_t n_linears
                             void *workspace, size_t workspace_bytes, quasar_sequence *seq);
 int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device,
                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Profiling aid (no passage of the paper stands behind it): quasar_sequence_run that also records
+ * when each workgroup passed the hand-over points of each phase, for a per-phase timeline of
+ * the launch.  stamps: device, quasar_sequence_stamps_bytes(seq) bytes, laid out
+ * [phase][workgroup][8] uint64 readings of the GPU's 100 MHz constant clock:
+ *   [0] began to wait for the phase's input      [1] saw the input complete
+ *   [2] had the input staged in LDS              [3] had summed its last tile
+ *   [4] had its outputs acknowledged and its completion flag raised      [5..7] unused
+ * Entries of workgroups without a share in a phase are left as they were (clear the buffer
+ * first).  Results are those of quasar_sequence_run; the stamps cost a few stores per phase.
+ */
+size_t quasar_sequence_stamps_bytes(const quasar_sequence *seq);
+int quasar_sequence_run_stamped(const quasar_sequence *seq, const void *plan_device,
+                                void *workspace, size_t workspace_bytes,
+                                uint64_t *stamps, size_t stamps_bytes, void *hip_stream);
 
 /*
  * ---- W8A8 form: int8 codes on both sides (Sec. 3.2 "Smoothing Transformation" and

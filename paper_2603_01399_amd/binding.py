@@ -21,7 +21,7 @@ PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 # every symbol declared in include/quasar.h
 EXPORTS = (
     "quasar_status_string", "quasar_version", "quasar_set_path", "quasar_get_path",
-    "quasar_set_tuning", "quasar_set_tuning_w4", "quasar_lmhead_verify_static",
+    "quasar_set_tuning", "quasar_set_tuning_w4", "quasar_lmhead_verify_static", "quasar_set_sequence_form", "quasar_sequence_stamps_bytes", "quasar_sequence_run_stamped",
     "quasar_packed_bytes", "quasar_packed_bytes_bf16", "quasar_workspace_bytes",
     "quasar_quantize_weights", "quasar_unpack_weights", "quasar_w8_linear", "quasar_lmhead_verify",
     "quasar_pack_bf16_weights", "quasar_bf16_linear", "quasar_bf16_lmhead_verify",
@@ -100,6 +100,9 @@ def _load() -> ctypes.CDLL:
     lib.quasar_sequence_workspace_bytes.restype = sz
     lib.quasar_sequence_prepare.argtypes = [vp, i64, vp, i64, vp, sz, vp, sz, vp]
     lib.quasar_sequence_run.argtypes = [vp, vp, vp, sz, vp]
+    lib.quasar_sequence_stamps_bytes.argtypes = [vp]
+    lib.quasar_sequence_stamps_bytes.restype = sz
+    lib.quasar_sequence_run_stamped.argtypes = [vp, vp, vp, sz, vp, sz, vp]
     lib.quasar_sequence_prepare_w8a8.argtypes = [vp, i64, vp, vp, vp, i64, vp, sz, vp, sz, vp]
     lib.quasar_sample_workspace_bytes.argtypes = [i64, i64]
     lib.quasar_sample_workspace_bytes.restype = sz
@@ -182,6 +185,10 @@ def get_path() -> int:
 
 def set_tuning(waves: int, wgs_per_cu: int, depth: int = 8) -> None:
     _check("quasar_set_tuning", _lib.quasar_set_tuning(waves, wgs_per_cu, depth))
+
+
+def set_sequence_form(workgroups_per_cu: int) -> None:
+    _check("quasar_set_sequence_form", _lib.quasar_set_sequence_form(workgroups_per_cu))
 
 
 def packed_bytes(N: int, K: int) -> int:
@@ -751,6 +758,10 @@ class Sequence:
         return self.handle.words[1]
 
     @property
+    def workgroups_per_cu(self) -> int:
+        return self.handle.words[14]
+
+    @property
     def n_barriers(self) -> int:
         """Phases that wait at a device-wide barrier (inputs in reused or partially overlapping buffers)."""
         return self.handle.words[12]
@@ -764,6 +775,16 @@ class Sequence:
         _check("quasar_sequence_run",
                _lib.quasar_sequence_run(ctypes.cast(ctypes.pointer(self.handle), ctypes.c_void_p), _ptr(self.plan),
                                         _ptr(self.workspace), self.workspace.numel(), _stream()))
+
+    def run_stamped(self) -> torch.Tensor:
+        """One step with per-phase time stamps: int64 tensor [nphases, workgroups, 8] (100 MHz ticks, 0 = no share)."""
+        hp = ctypes.cast(ctypes.pointer(self.handle), ctypes.c_void_p)
+        n = _lib.quasar_sequence_stamps_bytes(hp)
+        stamps = torch.zeros(n // 8, dtype=torch.int64, device=self.plan.device)
+        _check("quasar_sequence_run_stamped",
+               _lib.quasar_sequence_run_stamped(hp, _ptr(self.plan), _ptr(self.workspace), self.workspace.numel(),
+                                                _ptr(stamps), n, _stream()))
+        return stamps.view(self.nphases, -1, 8)
 
     def timed_out(self) -> bool:
         """True if a device-wide barrier of the last finished step gave up (synchronises)."""

@@ -503,10 +503,14 @@ int quasar_copy_stream(void *dst, const void *src, size_t bytes, void *hip_strea
 namespace {
 
 constexpr int kSeqWaves = 16;
-#ifndef QUASAR_SEQ_DEPTH
-#define QUASAR_SEQ_DEPTH 8
-#endif
-constexpr int kSeqDepth = QUASAR_SEQ_DEPTH;
+constexpr int kSeqDepth = 8;
+// the form with two alternating workgroups per compute unit (M <= 8): waves, ring depth, and the LDS
+// bytes that let exactly two such workgroups share a compute unit
+constexpr int kSeqWaves2 = 8;
+constexpr int kSeqDepth2 = 12;
+constexpr int kSeqMaxLds2 = 80 * 1024 - 1280;
+constexpr int kSeqMinLds2 = 56 * 1024;
+std::atomic<int> g_seq_form{0};          // 0: choose; 1 or 2: workgroups per compute unit wanted
 constexpr int kSeqMagic = 0x51534551;   // "QSEQ"
 // Bound on any single wait inside the whole-step launch: 200 ms of the 100 MHz constant clock.  A step takes
 // about 2 ms; a wait that long means a workgroup is not running at all, and the launch then ends with the
@@ -515,7 +519,7 @@ constexpr unsigned int kSeqSpinLimit = 20000000u;
 
 struct SeqHandle {   // lives in quasar_sequence::words
     int magic, nphases, M, MP, w16, xs_bytes, sc_bytes, lds_bytes, grid, has_verify, n_linears, a8;
-    int n_barriers, n_flag_waits;
+    int n_barriers, n_flag_waits, roles;
 };
 static_assert(sizeof(SeqHandle) <= sizeof(quasar_sequence), "handle must fit");
 
@@ -684,15 +688,46 @@ int launch_w4(const GemmParams &base, int M, hipStream_t stream, int *grid_out) 
 #undef QUASAR_LAUNCH_W4
 }
 
-template <int MP, bool W16, bool A8>
+template <int MP, bool W16, bool A8, int ROLES>
 int launch_sequence(const SeqHandle &h, const SeqParams &sp, hipStream_t st) {
-    auto kernel = stream_sequence_kernel<MP, W16, A8, kSeqWaves, kSeqDepth>;
+    constexpr int NW = ROLES == 2 ? kSeqWaves2 : kSeqWaves;
+    auto kernel = stream_sequence_kernel<MP, W16, A8, NW, (ROLES == 2 ? kSeqDepth2 : kSeqDepth), ROLES>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return QUASAR_ERR_HIP;
-    hipLaunchKernelGGL(sequence_reset_kernel, dim3(1), dim3(64), 0, st, sp.sync);
-    // Plain launch: one workgroup per compute unit is resident by construction (grid = number
-    // of compute units, one workgroup fits each); a cooperative launch would add ~20 us.
-    hipLaunchKernelGGL(kernel, dim3(h.grid), dim3(kSeqWaves * 64), (unsigned int)h.lds_bytes, st, sp);
+    hipLaunchKernelGGL(sequence_reset_kernel, dim3(1), dim3(256), 0, st, sp.sync);
+    // Plain launch: every workgroup is resident by construction (grid = ROLES workgroups per compute
+    // unit, and that many fit each; checked when the sequence is prepared); a cooperative launch
+    // would add ~20 us.
+    hipLaunchKernelGGL(kernel, dim3(h.grid), dim3(NW * 64), (unsigned int)h.lds_bytes, st, sp);
     return hipGetLastError() == hipSuccess ? QUASAR_OK : QUASAR_ERR_HIP;
+}
+
+// Workgroups of this kernel shape that fit one compute unit (0 on error).
+template <int MP, bool W16, bool A8, int ROLES>
+int sequence_residency(int lds_bytes) {
+    constexpr int NW = ROLES == 2 ? kSeqWaves2 : kSeqWaves;
+    auto kernel = stream_sequence_kernel<MP, W16, A8, NW, (ROLES == 2 ? kSeqDepth2 : kSeqDepth), ROLES>;
+    if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return 0;
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, NW * 64, (size_t)lds_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return per_cu;
+}
+template <int ROLES>
+int sequence_residency_of(int MP, bool w16, bool a8, int lds_bytes) {
+    if constexpr (ROLES == 2) {
+        if (MP != 8) return 0;
+        return w16 ? sequence_residency<8, true, false, 2>(lds_bytes)
+                   : (a8 ? sequence_residency<8, false, true, 2>(lds_bytes) : sequence_residency<8, false, false, 2>(lds_bytes));
+    } else {
+        if (w16) return MP == 8 ? sequence_residency<8, true, false, 1>(lds_bytes)
+                                : (MP == 16 ? sequence_residency<16, true, false, 1>(lds_bytes) : sequence_residency<32, true, false, 1>(lds_bytes));
+        if (a8) return MP == 8 ? sequence_residency<8, false, true, 1>(lds_bytes)
+                               : (MP == 16 ? sequence_residency<16, false, true, 1>(lds_bytes) : sequence_residency<32, false, true, 1>(lds_bytes));
+        return MP == 8 ? sequence_residency<8, false, false, 1>(lds_bytes)
+                       : (MP == 16 ? sequence_residency<16, false, false, 1>(lds_bytes) : sequence_residency<32, false, false, 1>(lds_bytes));
+    }
 }
 
 }  // namespace
@@ -706,12 +741,14 @@ size_t quasar_sequence_plan_bytes(int64_t n_linears) {
     return (size_t)(n_linears + 1) * sizeof(SeqPhase) + kSeqZeroBytes;   // phase table, block of zeros
 }
 
-// workspace: [256 B sync words][argmax partials][completion flags: (n_linears + 1) x grid]
+// workspace: [sync words, then one counter per compute-unit id][argmax partials][completion flags: (n_linears + 1) x grid]
+constexpr size_t kSeqHeaderBytes = 16 * 1024;
+static_assert((64 + kSeqCuSlots) * sizeof(unsigned int) <= kSeqHeaderBytes, "header holds the counters");
 constexpr size_t kSeqPartialBytes = (size_t)kMaxGrid * 32u * sizeof(unsigned long long);
 
 size_t quasar_sequence_workspace_bytes(int64_t n_linears, int64_t M) {
     if (M < 1 || M > 32 || n_linears < 0 || n_linears > (1 << 20)) return 0;
-    return 256 + kSeqPartialBytes + (size_t)(n_linears + 1) * kMaxGrid * sizeof(unsigned int);
+    return kSeqHeaderBytes + kSeqPartialBytes + (size_t)(n_linears + 1) * kMaxGrid * sizeof(unsigned int);
 }
 
 static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_linears, const float *const *smooth,
@@ -729,8 +766,8 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     if (a8 && w16) return QUASAR_ERR_DTYPE;
     const int MP = M <= 8 ? 8 : (M <= 16 ? 16 : 32);
     const int NB = MP == 32 ? 2 : 1;
-    const int G = device_cus();
-    if (G > kMaxGrid) return QUASAR_ERR_SHAPE;
+    const int G = device_cus();          // workgroups that share a phase (the grid is G times the workgroups per unit)
+    if (2 * G > kMaxGrid) return QUASAR_ERR_SHAPE;
 
     std::vector<SeqPhase> phases;
     // every output written so far in the sequence: (range, phase, segment, N, ldy, pointer)
@@ -878,7 +915,31 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
         if (sc > sc_max) sc_max = sc;
         if (ac > acc_max) acc_max = ac;
     }
-    const int lds = xs_max + sc_max + 2 * kSeqWaves * NB * 1024 + acc_max;
+    // One workgroup of 16 waves per compute unit, or two alternating ones of 8.  Measured on the 36-layer
+    // step: the alternating form is ~15% faster when the phases do not wait for each other (while one
+    // workgroup stages its activations the other streams) and ~25% slower on a chain of dependent phases
+    // (every hand-over costs the same round trips, and half the waves then work through each phase).  So it
+    // is chosen when at most a quarter of the phases wait, the shape allows it (M <= 8, everything fits
+    // half the LDS with the K chunks that the single calls use - about 64 KB of activations, K <= 4096 for
+    // bf16 activations - and two such workgroups are resident together), or when it is asked for.
+    int n_waits = 0;
+    for (const SeqPhase &p : phases) n_waits += p.wait != SEQ_WAIT_NONE;
+    const int form = g_seq_form.load();
+    const bool want2 = form == 2 || (form == 0 && 4 * n_waits <= (int)phases.size() && phases.size() >= 2);
+    int roles = 1;
+    int lds = xs_max + sc_max + 2 * kSeqWaves * NB * 1024 + acc_max;
+    if (MP == 8 && want2) {
+        int lds2 = xs_max + sc_max + kSeqWaves2 * NB * 1024 + acc_max;
+        if (lds2 < kSeqMinLds2) lds2 = kSeqMinLds2;
+        if (lds2 <= kSeqMaxLds2 && sequence_residency_of<2>(MP, w16, a8, lds2) >= 2) {
+            roles = 2;
+            lds = lds2;
+        } else if (form == 2) {
+            return QUASAR_ERR_SHAPE;
+        }
+    } else if (form == 2) {
+        return QUASAR_ERR_SHAPE;
+    }
     if (lds > kMaxLds) return QUASAR_ERR_SHAPE;
     if (hipMemcpy(plan_device, phases.data(), phases.size() * sizeof(SeqPhase), hipMemcpyHostToDevice) != hipSuccess)
         return QUASAR_ERR_HIP;
@@ -890,30 +951,16 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     if (hipDeviceSynchronize() != hipSuccess) return QUASAR_ERR_HIP;
     SeqHandle h{};
     h.magic = kSeqMagic; h.nphases = (int)phases.size(); h.M = (int)M; h.MP = MP; h.w16 = w16 ? 1 : 0;
-    h.xs_bytes = xs_max; h.sc_bytes = sc_max; h.lds_bytes = lds < kMinLds ? kMinLds : lds; h.grid = G;
+    h.xs_bytes = xs_max; h.sc_bytes = sc_max; h.lds_bytes = (roles == 1 && lds < kMinLds) ? kMinLds : lds;
+    h.grid = G * roles; h.roles = roles;
     h.has_verify = verify ? 1 : 0; h.n_linears = (int)n_linears; h.a8 = a8 ? 1 : 0;
     h.n_barriers = 0; h.n_flag_waits = 0;
     for (const SeqPhase &p : phases) {
         if (p.wait == SEQ_WAIT_BARRIER) ++h.n_barriers;
         if (p.wait == SEQ_WAIT_FLAGS) ++h.n_flag_waits;
     }
-    // The launch relies on every workgroup being resident at once (they wait for each other): one
-    // workgroup of this shape must fit a compute unit, and the grid is one workgroup per compute unit.
-    {
-        int per_cu = 0;
-        hipError_t e = hipSuccess;
-        const size_t lds_dyn = (size_t)h.lds_bytes;
-#define QUASAR_OCC(MPV, W16V, A8V)                                                                                   \
-        (allow_large_lds(reinterpret_cast<const void *>(stream_sequence_kernel<MPV, W16V, A8V, kSeqWaves, kSeqDepth>)) \
-             ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, stream_sequence_kernel<MPV, W16V, A8V, kSeqWaves, kSeqDepth>, \
-                                                            kSeqWaves * 64, lds_dyn)                                  \
-             : hipErrorUnknown)
-        if (w16) e = MP == 8 ? QUASAR_OCC(8, true, false) : (MP == 16 ? QUASAR_OCC(16, true, false) : QUASAR_OCC(32, true, false));
-        else if (a8) e = MP == 8 ? QUASAR_OCC(8, false, true) : (MP == 16 ? QUASAR_OCC(16, false, true) : QUASAR_OCC(32, false, true));
-        else e = MP == 8 ? QUASAR_OCC(8, false, false) : (MP == 16 ? QUASAR_OCC(16, false, false) : QUASAR_OCC(32, false, false));
-#undef QUASAR_OCC
-        if (e != hipSuccess || per_cu < 1) return QUASAR_ERR_HIP;
-    }
+    // The launch relies on every workgroup being resident at once (they wait for each other).
+    if (roles == 1 && sequence_residency_of<1>(MP, w16, a8, h.lds_bytes) < 1) return QUASAR_ERR_HIP;
     std::memset(seq, 0, sizeof(*seq));
     std::memcpy(seq, &h, sizeof(h));
     return QUASAR_OK;
@@ -934,38 +981,75 @@ int quasar_sequence_prepare_w8a8(const quasar_linear_desc *linears, int64_t n_li
                                  workspace, workspace_bytes, seq);
 }
 
-int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, void *workspace, size_t workspace_bytes,
-                        void *hip_stream) {
+static int sequence_run_impl(const quasar_sequence *seq, const void *plan_device, void *workspace, size_t workspace_bytes,
+                             uint64_t *stamps, size_t stamps_bytes, void *hip_stream) {
     if (!seq || !plan_device || !workspace) return QUASAR_ERR_NULL;
     SeqHandle h;
     std::memcpy(&h, seq, sizeof(h));
     if (h.magic != kSeqMagic || h.nphases < 1) return QUASAR_ERR_SHAPE;
     if (workspace_bytes < quasar_sequence_workspace_bytes(h.n_linears, h.M)) return QUASAR_ERR_WORKSPACE;
     if (!aligned(workspace, 16) || !aligned(plan_device, 16)) return QUASAR_ERR_ALIGN;
-    if (h.grid != device_cus()) return QUASAR_ERR_SHAPE;     // prepared for another device
+    if ((h.roles != 1 && h.roles != 2) || h.grid != device_cus() * h.roles) return QUASAR_ERR_SHAPE;   // prepared for another device
     SeqParams sp{};
     sp.phases = static_cast<const SeqPhase *>(plan_device);
     sp.nphases = h.nphases; sp.M = h.M; sp.xs_bytes = h.xs_bytes; sp.sc_bytes = h.sc_bytes;
     sp.sync = static_cast<unsigned int *>(workspace);
-    sp.partial = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(workspace) + 256);
-    sp.flags = reinterpret_cast<unsigned int *>(static_cast<unsigned char *>(workspace) + 256 + kSeqPartialBytes);
+    sp.partial = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(workspace) + kSeqHeaderBytes);
+    sp.flags = reinterpret_cast<unsigned int *>(static_cast<unsigned char *>(workspace) + kSeqHeaderBytes + kSeqPartialBytes);
     sp.spin_limit = kSeqSpinLimit;
+    sp.stamps = nullptr;
+    if (stamps) {
+        if (stamps_bytes < (size_t)h.nphases * h.grid * 8 * sizeof(uint64_t)) return QUASAR_ERR_WORKSPACE;
+        if (!aligned(stamps, 8)) return QUASAR_ERR_ALIGN;
+        sp.stamps = reinterpret_cast<unsigned long long *>(stamps);
+    }
     sp.zeros = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(plan_device) +
                                                (size_t)(h.n_linears + 1) * sizeof(SeqPhase));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (h.roles == 2) {
+        if (h.MP != 8) return QUASAR_ERR_SHAPE;
+        if (h.w16) return launch_sequence<8, true, false, 2>(h, sp, st);
+        if (h.a8) return launch_sequence<8, false, true, 2>(h, sp, st);
+        return launch_sequence<8, false, false, 2>(h, sp, st);
+    }
     if (h.w16) {
-        if (h.MP == 8) return launch_sequence<8, true, false>(h, sp, st);
-        if (h.MP == 16) return launch_sequence<16, true, false>(h, sp, st);
-        return launch_sequence<32, true, false>(h, sp, st);
+        if (h.MP == 8) return launch_sequence<8, true, false, 1>(h, sp, st);
+        if (h.MP == 16) return launch_sequence<16, true, false, 1>(h, sp, st);
+        return launch_sequence<32, true, false, 1>(h, sp, st);
     }
     if (h.a8) {
-        if (h.MP == 8) return launch_sequence<8, false, true>(h, sp, st);
-        if (h.MP == 16) return launch_sequence<16, false, true>(h, sp, st);
-        return launch_sequence<32, false, true>(h, sp, st);
+        if (h.MP == 8) return launch_sequence<8, false, true, 1>(h, sp, st);
+        if (h.MP == 16) return launch_sequence<16, false, true, 1>(h, sp, st);
+        return launch_sequence<32, false, true, 1>(h, sp, st);
     }
-    if (h.MP == 8) return launch_sequence<8, false, false>(h, sp, st);
-    if (h.MP == 16) return launch_sequence<16, false, false>(h, sp, st);
-    return launch_sequence<32, false, false>(h, sp, st);
+    if (h.MP == 8) return launch_sequence<8, false, false, 1>(h, sp, st);
+    if (h.MP == 16) return launch_sequence<16, false, false, 1>(h, sp, st);
+    return launch_sequence<32, false, false, 1>(h, sp, st);
+}
+
+int quasar_sequence_run(const quasar_sequence *seq, const void *plan_device, void *workspace, size_t workspace_bytes,
+                        void *hip_stream) {
+    return sequence_run_impl(seq, plan_device, workspace, workspace_bytes, nullptr, 0, hip_stream);
+}
+
+size_t quasar_sequence_stamps_bytes(const quasar_sequence *seq) {
+    if (!seq) return 0;
+    SeqHandle h;
+    std::memcpy(&h, seq, sizeof(h));
+    if (h.magic != kSeqMagic) return 0;
+    return (size_t)h.nphases * h.grid * 8 * sizeof(uint64_t);
+}
+
+int quasar_sequence_run_stamped(const quasar_sequence *seq, const void *plan_device, void *workspace,
+                                size_t workspace_bytes, uint64_t *stamps, size_t stamps_bytes, void *hip_stream) {
+    if (!stamps) return QUASAR_ERR_NULL;
+    return sequence_run_impl(seq, plan_device, workspace, workspace_bytes, stamps, stamps_bytes, hip_stream);
+}
+
+int quasar_set_sequence_form(int workgroups_per_cu) {
+    if (workgroups_per_cu < 0 || workgroups_per_cu > 2) return QUASAR_ERR_SHAPE;
+    g_seq_form = workgroups_per_cu;
+    return QUASAR_OK;
 }
 
 int quasar_quantize_activations(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const float *smooth,

@@ -422,9 +422,12 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                         f32x4 rsum[NB];
 #pragma unroll
                         for (int nb = 0; nb < NB; ++nb) {
-                            rsum[nb] = st[nb * 64 + lane];
+                            // fixed order: neighbouring waves in pairs, then the pair sums one after the
+                            // other (the whole-step kernel's 8-wave form adds each pair inside one wave)
+                            rsum[nb] = st[nb * 64 + lane] + st[(NB + nb) * 64 + lane];
 #pragma unroll
-                            for (int ww = 1; ww < NW; ++ww) rsum[nb] += st[(ww * NB + nb) * 64 + lane];
+                            for (int ww = 2; ww < NW; ww += 2)
+                                rsum[nb] += st[(ww * NB + nb) * 64 + lane] + st[((ww + 1) * NB + nb) * 64 + lane];
                             if (p.C > 1) {
                                 f32x4 *a = accs + (tl * NB + nb) * 64 + lane;
                                 if (c > 0) rsum[nb] += *a;

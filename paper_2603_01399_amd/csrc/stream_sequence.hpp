@@ -78,11 +78,16 @@ struct SeqParams {
     int M;
     int xs_bytes;            // LDS reserved for activations (max over phases)
     int sc_bytes;            // LDS reserved for row scales (max over phases)
-    unsigned int *sync;      // [0] arrival counter, [1] error flag (both zero at launch), [2] launch epoch
+    unsigned int *sync;      // [0] arrival counter, [1] error flag (both zero at launch), [2] launch epoch,
+                             // [8], [9] members of role 0 / 1 so far, [64 + id] workgroups seen on compute unit id
     unsigned int *flags;     // [nphases][gridDim.x]: epoch of the launch in which the workgroup finished the phase
     unsigned long long *partial;   // argmax phase: [gridDim.x][MP] packed (logit, index) keys
     unsigned int spin_limit; // bound on the time one wait may take, in ticks of the 100 MHz constant clock
     const u32x4 *zeros;      // 1 KB of zeros, never written: what a slot without a weight step loads
+    unsigned long long *stamps;   // optional (nullptr: none): [nphases][gridDim.x][8] times of the 100 MHz clock at
+                                  // which a workgroup [0] began to wait for a phase's input, [1] saw it complete,
+                                  // [2] had it staged, [3] had summed its last tile, [4] had its outputs
+                                  // acknowledged and its flag raised; untouched where it has no share
 };
 
 // Data that crosses from one phase to a later one inside the launch (outputs read as the
@@ -102,6 +107,22 @@ __device__ __forceinline__ u32x4 coherent_load_u32x4(const void *p) {
     const unsigned long long hi = coherent_load_u64(static_cast<const unsigned long long *>(p) + 1);
     return u32x4{(unsigned int)lo, (unsigned int)(lo >> 32), (unsigned int)hi, (unsigned int)(hi >> 32)};
 }
+// 16 bytes per lane from gbase + lane_offset (gbase wave-uniform) straight into LDS at lds_addr + 16 * lane,
+// without passing through registers.  Inline assembly on purpose: when the compiler sees a direct-to-LDS
+// load anywhere in a kernel it makes every LDS read wait for ALL outstanding vector memory loads (it
+// cannot tell which loads write LDS), which would drain the weight ring at every slot.  The caller waits
+// for these loads explicitly (vmcnt(0)) before anybody reads the bytes.
+__device__ __forceinline__ void load_to_lds_16(unsigned long long gbase, unsigned int lane_offset, unsigned int lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_offset), "s"(gbase), "s"(lds_addr)
+                 : "memory");   // (M0 is reserved: the compiler keeps nothing in it across statements)
+}
+__device__ __forceinline__ unsigned int lds_address_of(const unsigned char *p) {
+    return __builtin_amdgcn_readfirstlane(
+        (unsigned int)(unsigned long long)((const __attribute__((address_space(3))) unsigned char *)p));
+}
+
 // All workgroups of the launch meet.  Every wave first waits until its own (coherent) stores
 // have been acknowledged, so whatever the workgroup wrote is readable device-wide once the
 // arrival counter has been bumped.  Polling is bounded in TIME (spin_limit ticks of the 100 MHz
@@ -127,31 +148,48 @@ __device__ __forceinline__ void grid_barrier(unsigned int *sync, unsigned int ta
 
 // Activation pieces a thread holds per staging batch; ring slots are refilled in groups of kSeqRefillGroup,
 // after the group's last slot has been used.
-constexpr int kSeqStageBatch = 8;
+constexpr int kSeqStageBatch = 2;
 constexpr int kSeqRefillGroup = 4;
 
 // A8 selects the W8A8 form of the linears: the activations are smoothed and quantised per
 // token while they are staged (same arithmetic as stream_w8a8.hpp), the weight step goes
 // straight into the int8 matrix core, the cross-wave sums are exact integers.
-template <int MP, bool W16, bool A8, int NW, int D>
-__global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParams sp) {
+//
+// ROLES == 2 (two workgroups of 8 waves per compute unit): the workgroups of a compute unit take
+// the phases in turn.  While one of them waits for the activations of its phase, stages them and
+// computes, the other one - whose next phase is the one after - already has its ring full of that
+// phase's weights and keeps loading as slots free up, so the memory pipeline has work across the
+// hand-over.  A workgroup learns at start which compute unit it runs on and takes the role nobody
+// there has yet; roles are capped at half the grid each, so the split is even wherever the
+// workgroups land (placement only matters for speed).  Each wave covers the K range that two waves
+// of the 16-wave form cover and adds their two partial sums in the same order, so the results are
+// the same bits.
+constexpr int kSeqCuSlots = 2048;     // distinct compute-unit ids (XCC, shader engine, unit)
+
+template <int MP, bool W16, bool A8, int NW, int D, int ROLES>
+__global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_kernel(const SeqParams sp) {
     extern __shared__ __align__(16) unsigned char lds[];
     static_assert(!(W16 && A8), "the W8A8 form needs int8 weights");
     constexpr int NB = (MP == 32) ? 2 : 1;
     constexpr int PPS = (W16 || A8) ? 4 : 8;   // 16-byte LDS pieces per step and token
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
     constexpr int KSTEP = W16 ? kStepK16 : kStepK8;
+    // pieces per thread and batch of the staging path through registers (only the barrier-ordered,
+    // coherent reads take it; everything else goes straight to LDS): small batches, few registers
     constexpr int XB = kSeqStageBatch;
+    constexpr int NPAR = ROLES == 2 ? 1 : 2;   // copies of the cross-wave staging area
+    static_assert(ROLES == 1 || ROLES == 2, "one workgroup per compute unit, or two that alternate");
+    static_assert((ROLES == 1 && NW == 16) || (ROLES == 2 && NW == 8), "wave count of each form");
     constexpr int GR = kSeqRefillGroup;
     static_assert(GR >= 1 && (GR & (GR - 1)) == 0 && D % GR == 0, "refill groups tile the ring");
     constexpr int nthreads = NW * 64;
-    static_assert(NW == 16, "the in-kernel second stage of the verify phase assumes 1024 threads");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, mcol = lane & 15;
     const int G = gridDim.x, b = blockIdx.x;
+    const int GW = G / ROLES;          // workgroups that share a phase
     const int M = sp.M;
     const int nph = sp.nphases;
     const const_phase_ptr phases = (const_phase_ptr)(unsigned long long)sp.phases;
@@ -162,7 +200,36 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     float *tok_dx = reinterpret_cast<float *>(lds + sp.xs_bytes + sp.sc_bytes - 256);                  // [32]
     unsigned int *tok_amax = reinterpret_cast<unsigned int *>(lds + sp.xs_bytes + sp.sc_bytes - 128);  // [32]
     f32x4 *stage = reinterpret_cast<f32x4 *>(lds + sp.xs_bytes + sp.sc_bytes);   // [2][NW][NB][64]
-    f32x4 *accs = stage + 2 * NW * NB * 64;                                      // [ntiles][NB][64] (C > 1)
+    f32x4 *accs = stage + NPAR * NW * NB * 64;                                   // [ntiles][NB][64] (C > 1)
+
+    // role (which phases) and rank (which tiles) of this workgroup
+    int role = 0, rk = b;
+    if constexpr (ROLES == 2) {
+        unsigned int *box = reinterpret_cast<unsigned int *>(stage);
+        if (tid == 0) {
+            const unsigned int cu = __smid() & (unsigned int)(kSeqCuSlots - 1);
+            const unsigned int seen = __hip_atomic_fetch_add(as_global(&sp.sync[64 + cu]), 1u, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT);
+            unsigned int r = seen & 1u;
+            unsigned int k = __hip_atomic_fetch_add(as_global(&sp.sync[8 + r]), 1u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+            if (k >= (unsigned int)GW) {       // that role is full: the other one cannot be
+                r ^= 1u;
+                k = __hip_atomic_fetch_add(as_global(&sp.sync[8 + r]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            box[0] = r;
+            box[1] = k < (unsigned int)GW ? k : 0u;
+        }
+        lds_barrier();
+        role = __builtin_amdgcn_readfirstlane((int)box[0]);
+        rk = __builtin_amdgcn_readfirstlane((int)box[1]);
+        lds_barrier();
+    }
+    auto mine = [&](int ph) -> bool { return ROLES == 1 || (ph & 1) == role; };
+    auto stamp = [&](int ph, int what) {
+        if (sp.stamps && tid == 0)
+            *as_global(sp.stamps + ((long long)ph * G + b) * 8 + what) = __builtin_amdgcn_s_memrealtime();
+    };
 
     // Activations produced inside the launch are later read through the caches.  Lines of an
     // earlier launch (same addresses, old values) cannot be hit: the packet processor
@@ -207,9 +274,9 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             if (l_ph < nph && l_c >= phases[l_ph].C) { ++l_ph; l_c = 0; }
             if (l_ph >= nph) { l_ntiles = 0; l_spw = 0; return; }
             const auto &P = phases[l_ph];
-            l_t0 = (int)(((unsigned int)P.T * (unsigned int)b) / (unsigned int)G);   // the host checks T * G < 2^31
-            l_ntiles = (int)(((unsigned int)P.T * (unsigned int)(b + 1)) / (unsigned int)G) - l_t0;
-            if (l_ntiles == 0) { l_c = P.C - 1; continue; }
+            l_t0 = (int)(((unsigned int)P.T * (unsigned int)rk) / (unsigned int)GW);   // the host checks T * G < 2^31
+            l_ntiles = (int)(((unsigned int)P.T * (unsigned int)(rk + 1)) / (unsigned int)GW) - l_t0;
+            if (l_ntiles == 0 || !mine(l_ph)) { l_c = P.C - 1; continue; }
             const int scc = min(P.SC, P.S - l_c * P.SC);
             l_s_lo = (scc * w) / NW;
             l_spw = (scc * (w + 1)) / NW - l_s_lo;
@@ -231,6 +298,7 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 if (l_t0 + l_tl == l_seg_end) l_retile(); else l_wt += l_stride;
             } else {
                 const int pad = l_in_pad ? 0 : (-(l_ntiles * max(l_spw, 1))) & (GR - 1);
+
                 if (pad > 0) {
                     l_in_pad = true;
                     l_base = zeros;
@@ -278,12 +346,15 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     unsigned int barriers_done = 0;
     int parity = 0;
     f32x4 acc[NB];
+    [[maybe_unused]] f32x4 acc_lo[NB];   // ROLES == 2: the sum over the first half of this wave's K range
+    [[maybe_unused]] int c_h0 = 0, c_half = 0;   // steps in that half; slots until it ends
     i32x4 acci[NB];          // W8A8: exact integer sums
     float bestv[NB];
     unsigned int besti[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc_lo[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
         acci[nb] = i32x4{0, 0, 0, 0};
         bestv[nb] = -__builtin_inff();
         besti[nb] = 0x7FFFFFFFu;
@@ -295,9 +366,31 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     // stage one activation chunk.  `coherent` reads go past the L2 (needed when the buffer may
     // have been cached before it was last written: barrier-ordered, reused buffers); otherwise
     // the 32 compute units of an XCD share one fetch of the activations through their L2.
+    [[maybe_unused]] const unsigned int lds_base = lds_address_of(lds);
     auto x_stage = [&](const auto &P, int c, bool coherent) {
         const int scc = min(P.SC, P.S - c * P.SC);
         const int npieces = scc * PPS * MP;
+        if constexpr (!A8) {
+            if (!coherent) {
+                // 64 pieces (1 KB of LDS) per instruction: lane l fetches token l % MP (rows past M repeat
+                // row M - 1: their results are never used), 8 columns at 8 * (l / MP); waves take turns
+                const unsigned int x_voff = (unsigned int)min(lane & (MP - 1), M - 1) * (unsigned int)P.ldx * 2u +
+                                            16u * (unsigned int)(lane >> LMP);
+                const unsigned long long x0 = reinterpret_cast<unsigned long long>(P.x) +
+                                              2ull * (unsigned long long)c * P.SC * KSTEP;
+                const int ninstr = (npieces + 63) >> 6;
+                for (int i = w; i < ninstr; i += NW) {
+                    const unsigned long long gb = x0 + (unsigned long long)i * (unsigned long long)(1024 / MP);
+                    const unsigned int glo = __builtin_amdgcn_readfirstlane((unsigned int)gb);
+                    const unsigned int ghi = __builtin_amdgcn_readfirstlane((unsigned int)(gb >> 32));
+                    const unsigned long long gbase = ((unsigned long long)ghi << 32) | glo;
+                    const unsigned int laddr = lds_base + (unsigned int)i * 1024u;
+                    if (i * 64 + 64 <= npieces) load_to_lds_16(gbase, x_voff, laddr);
+                    else if (i * 64 + lane < npieces) load_to_lds_16(gbase, x_voff, laddr);
+                }
+                return;
+            }
+        }
         for (int base = 0; base < npieces; base += nthreads * XB) {
             u32x4 v[XB];
 #pragma unroll
@@ -409,17 +502,19 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     // its flag for phase `pp` in this launch
     auto flags_wait = [&](int pp) {
         if (w != 0) return;
-        const unsigned int *row = sp.flags + (long long)pp * G;
+        const unsigned int *row = sp.flags + (long long)pp * G;   // the first GW entries: ranks of the phase's role
         const unsigned long long t_begin = __builtin_amdgcn_s_memrealtime();
-        for (int t0 = 4 * lane; t0 < G; t0 += 256) {
+        for (int t0 = 4 * lane; t0 < GW; t0 += 256) {
             for (;;) {
                 unsigned int f[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    f[i] = t0 + i < G ? __hip_atomic_load(as_global(row + t0 + i), __ATOMIC_RELAXED,
+                    f[i] = t0 + i < GW ? __hip_atomic_load(as_global(row + t0 + i), __ATOMIC_RELAXED,
                                                           __HIP_MEMORY_SCOPE_AGENT)
                                       : epoch;
                 if (f[0] == epoch && f[1] == epoch && f[2] == epoch && f[3] == epoch) break;
+                // (the error word is only read on this path: a load still pending when the loop is left would
+                // make the compiler give up counting the ring's outstanding loads and drain it at every slot)
                 if (__builtin_amdgcn_s_memrealtime() - t_begin > sp.spin_limit ||
                     __hip_atomic_load(as_global(&sp.sync[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
                     __hip_atomic_store(as_global(&sp.sync[1]), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -443,6 +538,8 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
     bool stored = false;   // this wave has output stores in flight
     // end of a phase: raise this workgroup's completion flag if a later phase waits for it
     auto phase_end = [&](int ph) {
+        stamp(ph, 3);
+        if (!phases[ph].publish) stamp(ph, 4);
         if (phases[ph].publish) {
             // the output stores have been acknowledged before the flag goes up (only waves that
             // stored wait: for the others this would be a wait for their weight loads)
@@ -450,8 +547,9 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             stored = false;
             lds_barrier();
             if (tid == 0)
-                __hip_atomic_store(as_global(sp.flags + (long long)ph * G + b), epoch, __ATOMIC_RELAXED,
+                __hip_atomic_store(as_global(sp.flags + (long long)ph * G + rk), epoch, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
+            stamp(ph, 4);
         }
     };
     // after the last phase, if it was the vocabulary phase: publish argmax partials, meet, and
@@ -485,29 +583,31 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
         grid_barrier(sp.sync, barriers_done * (unsigned int)G, sp.spin_limit);
         if (b == 0) {
             int32_t *am = reinterpret_cast<int32_t *>(stage);
-            const int m = tid >> 5, sub = tid & 31;
-            unsigned long long key = 0ull;
-            if (m < M)
-                for (int i0 = sub; i0 < G; i0 += 32 * 8) {
-                    unsigned long long o[8];   // eight independent loads in flight per lane
+            const int sub = tid & 31;
+            for (int m = tid >> 5; m < MP; m += nthreads / 32) {     // 32 lanes per position
+                unsigned long long key = 0ull;
+                if (m < M)
+                    for (int i0 = sub; i0 < G; i0 += 32 * 8) {
+                        unsigned long long o[8];   // eight independent loads in flight per lane
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int i = i0 + 32 * u;
-                        o[u] = i < G ? coherent_load_u64(sp.partial + (long long)i * MP + m) : 0ull;
+                        for (int u = 0; u < 8; ++u) {
+                            const int i = i0 + 32 * u;
+                            o[u] = i < G ? coherent_load_u64(sp.partial + (long long)i * MP + m) : 0ull;
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) key = o[u] > key ? o[u] : key;
                     }
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) key = o[u] > key ? o[u] : key;
+                for (int off = 16; off >= 1; off >>= 1) {
+                    const unsigned long long o = shfl_xor_u64(key, off);
+                    key = o > key ? o : key;
                 }
-#pragma unroll
-            for (int off = 16; off >= 1; off >>= 1) {
-                const unsigned long long o = shfl_xor_u64(key, off);
-                key = o > key ? o : key;
-            }
-            if (m < M && sub == 0) {
-                unsigned int idx = argmax_key_index(key);
-                if (idx >= (unsigned int)P.V) idx = 0;
-                am[m] = (int32_t)idx;
-                *as_global(P.out_argmax + m) = (int32_t)idx;
+                if (m < M && sub == 0) {
+                    unsigned int idx = argmax_key_index(key);
+                    if (idx >= (unsigned int)P.V) idx = 0;
+                    am[m] = (int32_t)idx;
+                    *as_global(P.out_argmax + m) = (int32_t)idx;
+                }
             }
             lds_barrier();
             if (tid == 0) {
@@ -538,30 +638,42 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             if (c_c == 0) {
                 c_C = P.C;
                 c_kind = P.kind;
-                c_t0 = (int)(((unsigned int)P.T * (unsigned int)b) / (unsigned int)G);
-                c_ntiles = (int)(((unsigned int)P.T * (unsigned int)(b + 1)) / (unsigned int)G) - c_t0;
+                c_t0 = (int)(((unsigned int)P.T * (unsigned int)rk) / (unsigned int)GW);
+                c_ntiles = (int)(((unsigned int)P.T * (unsigned int)(rk + 1)) / (unsigned int)GW) - c_t0;
                 if (P.wait == SEQ_WAIT_BARRIER) {
                     ++barriers_done;
                     grid_barrier(sp.sync, barriers_done * (unsigned int)G, sp.spin_limit);
-                } else {
+                }
+                if (!mine(c_ph)) {     // the other role's phase: only its device-wide barrier is shared
+                    ++c_ph;
+                    continue;
+                }
+                stamp(c_ph, 0);
+                if (P.wait != SEQ_WAIT_BARRIER) {
                     if (P.wait == SEQ_WAIT_FLAGS) {
                         flags_wait(P.producer[0]);
                         if (P.producer[1] >= 0) flags_wait(P.producer[1]);
                     }
                     lds_barrier();   // flags seen by all; the previous phase's last epilogue has read its scales
                 }
+                stamp(c_ph, 1);
                 if (c_ntiles == 0) {   // nothing to do here but the waits
                     c_c = c_C - 1;
                     c_leave();
                     continue;
                 }
-                scale_stage(P, c_t0, c_ntiles);
+                if constexpr (A8) scale_stage(P, c_t0, c_ntiles);
                 if constexpr (A8) x_scan(P, P.wait == SEQ_WAIT_BARRIER);
             }
             const int scc = min(P.SC, P.S - c_c * P.SC);
             const int s_lo = (scc * w) / NW;
             const int spw = (scc * (w + 1)) / NW - s_lo;
             c_nsl = max(spw, 1);
+            if constexpr (ROLES == 2) {
+                // the first of the two 16th-parts of the chunk that this wave covers
+                c_h0 = (scc * (2 * w + 1)) / (2 * NW) - s_lo;
+                c_half = c_h0 > 0 ? c_h0 : kForever;
+            }
             c_xinc = spw > 0 ? (unsigned int)(PPS * MP * 16) : 0u;
             c_x0 = spw > 0 ? (unsigned int)s_lo * (unsigned int)(PPS * MP * 16) : 0u;
             c_tl = 0;
@@ -570,11 +682,38 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
             unit_left = (c_ntiles * c_nsl + GR - 1) & ~(GR - 1);
             nocomp = false;
             c_reseg();
-            if constexpr (A8) x_quant(P, c_c, P.wait == SEQ_WAIT_BARRIER);
-            else x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
+            if constexpr (A8) {
+                x_quant(P, c_c, P.wait == SEQ_WAIT_BARRIER);
+            } else {
+                // activations and row scales are requested together and waited for once: one round trip,
+                // not two (the activations first: they go straight to LDS, so no loaded value is held across
+                // their issue loop).  One load of two scales per thread covers the scales in all but huge
+                // shares; the member matrix of a thread's row is picked among values held in scalar
+                // registers - looking it up in the phase table per lane would cost a round trip of its own.
+                x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
+                if constexpr (!W16) {
+                    if (c_c == 0) {
+                        if (c_ntiles * (kTileRows / 2) <= nthreads) {
+                            if (tid < c_ntiles * (kTileRows / 2)) {
+                                const int t = c_t0 + (tid >> 3);
+                                const uint16_t *base = P.seg[0].scales;
+                                int tb = 0;
+                                if (P.nseg > 1 && t >= P.seg[1].tile_begin) { base = P.seg[1].scales; tb = P.seg[1].tile_begin; }
+                                if (P.nseg > 2 && t >= P.seg[2].tile_begin) { base = P.seg[2].scales; tb = P.seg[2].tile_begin; }
+                                if (P.nseg > 3 && t >= P.seg[3].tile_begin) { base = P.seg[3].scales; tb = P.seg[3].tile_begin; }
+                                reinterpret_cast<unsigned int *>(sc_lds)[tid] = *as_global(reinterpret_cast<const unsigned int *>(
+                                    base + (long long)(t - tb) * kTileRows + ((2 * tid) & 15)));
+                            }
+                        } else {
+                            scale_stage(P, c_t0, c_ntiles);
+                        }
+                    }
+                }
+            }
             // known-empty load queue: keeps the counted waits of the ring exact (see stream_gemm.hpp)
             __builtin_amdgcn_s_waitcnt(0x0F70);
             lds_barrier();
+            if (c_c == 0) stamp(c_ph, 2);
             return true;
         }
     };
@@ -638,15 +777,29 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                 l_base += l_inc;
                 if (__builtin_expect(--l_left == 0, 0)) l_event();
             }
+            if constexpr (ROLES == 2 && !A8) {
+                if (!nocomp && __builtin_expect(--c_half == 0, 0)) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        acc_lo[nb] = acc[nb];
+                        acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+            }
             if (!nocomp && __builtin_expect(--c_left == 0, 0)) {
                 // ---- tile end: cross-wave sum through LDS, fixed order (W8A8: exact integers)
                 using acc_t = std::conditional_t<A8, i32x4, f32x4>;
                 acc_t *st = reinterpret_cast<acc_t *>(stage) + (parity * NW) * NB * 64;
+                if constexpr (NPAR == 1) lds_barrier();   // the previous tile's sums have been read
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     if constexpr (A8) {
                         st[(w * NB + nb) * 64 + lane] = acci[nb];
                         acci[nb] = i32x4{0, 0, 0, 0};
+                    } else if constexpr (ROLES == 2) {
+                        st[(w * NB + nb) * 64 + lane] = acc_lo[nb] + acc[nb];
+                        acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        acc_lo[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
                     } else {
                         st[(w * NB + nb) * 64 + lane] = acc[nb];
                         acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -660,9 +813,17 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                     acc_t rsum[NB];
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
-                        rsum[nb] = st[nb * 64 + lane];
+                        if constexpr (ROLES == 2 || A8) {
+                            rsum[nb] = st[nb * 64 + lane];
 #pragma unroll
-                        for (int ww = 1; ww < NW; ++ww) rsum[nb] += st[(ww * NB + nb) * 64 + lane];
+                            for (int ww = 1; ww < NW; ++ww) rsum[nb] += st[(ww * NB + nb) * 64 + lane];
+                        } else {
+                            // pairs of neighbouring waves first, then the pair sums in order
+                            rsum[nb] = st[nb * 64 + lane] + st[(NB + nb) * 64 + lane];
+#pragma unroll
+                            for (int ww = 2; ww < NW; ww += 2)
+                                rsum[nb] += st[(ww * NB + nb) * 64 + lane] + st[((ww + 1) * NB + nb) * 64 + lane];
+                        }
                         if (c_C > 1) {
                             acc_t *a = reinterpret_cast<acc_t *>(accs) + (c_tl * NB + nb) * 64 + lane;
                             if (c_c > 0) rsum[nb] += *a;
@@ -713,7 +874,8 @@ __global__ __launch_bounds__(NW * 64) void stream_sequence_kernel(const SeqParam
                         }
                     }
                 }
-                parity ^= 1;
+                if constexpr (NPAR == 2) parity ^= 1;
+                if constexpr (ROLES == 2) c_half = c_h0 > 0 ? c_h0 : kForever;
                 // advance the compute front; after the unit's last tile only padding is left
                 if (++c_tl >= c_ntiles) {
                     nocomp = true;
@@ -751,7 +913,10 @@ __global__ void sequence_reset_kernel(unsigned int *sync) {
         sync[0] = 0u;
         sync[1] = 0u;
         sync[2] = sync[2] + 1u;
+        sync[8] = 0u;
+        sync[9] = 0u;
     }
+    for (int i = threadIdx.x; i < kSeqCuSlots; i += blockDim.x) sync[64 + i] = 0u;
 }
 
 }  // namespace quasar

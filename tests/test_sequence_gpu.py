@@ -364,3 +364,89 @@ def test_sequence_argument_errors(qb):
     with pytest.raises(qb.QuasarError) as e:
         qb.Sequence([(x, wq, sc, 256, y), (y, wb, None, 256, torch.zeros_like(y))])   # mixed weight types
     assert e.value.status == 5
+
+
+@pytest.mark.parametrize("M,hidden,kv,inter,bf16", [
+    (8, 512, 128, 8320, False),     # K = 8320 in two chunks of 65 KB
+    (5, 1280, 256, 4096, False),    # uneven step shares, ragged M
+    (8, 256, 64, 768, True),        # bf16 weights
+    (1, 4096, 1024, 1024, False),   # full-size K: 64 KB of activations beside the second workgroup
+])
+def test_sequence_two_workgroups_per_compute_unit_same_bits(qb, M, hidden, kv, inter, bf16):
+    """The form with two alternating workgroups of 8 waves per compute unit (asked for explicitly: a
+    chain of dependent phases would not choose it) against the single calls and against the form
+    with one workgroup of 16 waves: identical bits, including ping-pong buffers (barriers) and the
+    vocabulary phase; the time stamps of a stamped run are ordered."""
+    print("sequence two workgroups per unit", M, hidden, kv, inter, bf16, flush=True)
+    n_layers, V = 2, 2048
+    layers = build_model(qb, n_layers, hidden, kv, inter, seed=9300 + M, bf16=bf16)
+    x0 = synth.activations_bf16(M, hidden, seed=9310 + M)
+    wv = synth.normal_weights(V, hidden, seed=9320 + M, std=1.0 / np.sqrt(hidden))
+    head = (qb.pack_bf16_weights(f32_to_dev(wv)), None) if bf16 else qb.quantize_weights(f32_to_dev(wv))
+    draft = i32_to_dev(np.arange(1, M, dtype=np.int32)) if M > 1 else None
+    results = {}
+    try:
+        for form in (2, 1):
+            qb.set_sequence_form(form)
+            bufs, h_dev = gpu_buffers(layers, M, x0)
+            am = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+            acc = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+            seq = qb.Sequence(linear_list(layers, bufs), verify=(h_dev, head[0], head[1], V, draft, am, acc))
+            assert seq.workgroups_per_cu == form
+            for _ in range(3):
+                seq.run()
+            stamps = seq.run_stamped().cpu().numpy()
+            torch.cuda.synchronize()
+            assert not seq.timed_out()
+            results[form] = (bufs, am, acc)
+            assert stamps.shape == (seq.nphases, seq.workgroups_per_cu * torch.cuda.get_device_properties(0).multi_processor_count, 8)
+            took = stamps[:, :, 2] > 0                      # workgroups with a share in the phase
+            assert took.any(axis=1).all()
+            for a, b in ((0, 1), (1, 2), (2, 3), (3, 4)):
+                assert (stamps[:, :, a][took] <= stamps[:, :, b][took]).all(), (a, b)
+            # a phase's input was seen complete only after every producer had raised its flag
+            for p in range(1, seq.nphases):
+                if took[p].any() and took[p - 1].any() and p % 4 != 0:
+                    assert stamps[p, :, 1][took[p]].min() >= stamps[p - 1, :, 3][took[p - 1]].max()
+    finally:
+        qb.set_sequence_form(0)
+    bufs2, h2 = gpu_buffers(layers, M, x0)
+    for (x, wp, sc, N, y) in linear_list(layers, bufs2):
+        qb.bf16_linear(x, wp, N, y) if bf16 else qb.w8_linear(x, wp, sc, N, y)
+    ws = qb.make_workspace(M, V, hidden)
+    am2, acc2 = (qb.bf16_lmhead_verify(h2, head[0], V, draft, ws) if bf16
+                 else qb.lmhead_verify(h2, head[0], head[1], V, draft, ws))
+    torch.cuda.synchronize()
+    for form in (2, 1):
+        bufs, am, acc = results[form]
+        for li in range(n_layers):
+            for name in ("q", "k", "v", "o", "gate", "up", "down"):
+                assert torch.equal(bufs[li][name].view(torch.int16), bufs2[li][name].view(torch.int16)), (form, li, name)
+        assert torch.equal(am, am2) and torch.equal(acc, acc2), form
+
+
+def test_sequence_of_independent_linears_takes_the_alternating_form(qb):
+    """Phases that do not wait for each other (every linear reads a resident input): prepare picks two
+    workgroups per compute unit by itself; bits equal the single calls; W8A8 form too."""
+    print("sequence independent phases", flush=True)
+    from oracle import quasar_w8a8_ref as a8
+    M, K = 8, 1024
+    xs = [bf16_to_dev(synth.activations_bf16(M, K, seed=9400 + i)) for i in range(4)]
+    ws = []
+    for i in range(4):
+        w = synth.normal_weights(512, K, seed=9410 + i, std=1.0 / np.sqrt(K))
+        ws.append((ref.quantize_weights(w), qb.quantize_weights(f32_to_dev(w))))
+    for w8a8 in (False, True):
+        ys = [torch.zeros((M, 512), dtype=torch.bfloat16, device="cuda") for _ in range(4)]
+        seq = qb.Sequence([(xs[i], ws[i][1][0], ws[i][1][1], 512, ys[i]) for i in range(4)], w8a8=w8a8)
+        assert seq.nphases == 4 and seq.n_flag_waits == 0 and seq.n_barriers == 0
+        assert seq.workgroups_per_cu == 2
+        for _ in range(2):
+            seq.run()
+        torch.cuda.synchronize()
+        assert not seq.timed_out()
+        for i in range(4):
+            one = qb.w8a8_linear(xs[i], ws[i][1][0], ws[i][1][1], 512) if w8a8 else qb.w8_linear(xs[i], ws[i][1][0], ws[i][1][1], 512)
+            assert torch.equal(one.view(torch.int16), ys[i].view(torch.int16)), (w8a8, i)
+            if w8a8:
+                assert np.array_equal(bf16_to_host(ys[i]), a8.w8a8_linear(bf16_to_host(xs[i]), ws[i][0][0], ws[i][0][1])), i
