@@ -29,6 +29,48 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def timeline_summary(seq, L, log, np, torch):
+    """Per-phase timeline of one whole-step launch from the kernel's own time stamps (100 MHz clock).
+
+    For each kind of phase (q|k|v, o, gate|up, down), averaged over the layers after the first:
+      spread   last minus first workgroup to finish the PREVIOUS phase (what the slowest producer costs)
+      ack      a workgroup's last tile summed -> its outputs acknowledged and its flag raised
+      detect   last producer flag raised -> a consumer has seen all flags (mean over consumers)
+      stage    input seen complete -> activations (and row scales) staged in LDS
+      stream   staged -> last tile summed (mean, fastest and slowest workgroup)
+      period   end of the previous phase -> end of this one (slowest workgroups): the phase's share of the step
+    """
+    for _ in range(3):
+        seq.run()
+    st = seq.run_stamped().cpu().numpy().astype(np.float64) / 100.0        # us
+    torch.cuda.synchronize()
+    assert not seq.timed_out()
+    nph = st.shape[0]
+    took = st[:, :, 2] > 0
+    t0 = st[0][took[0]][:, 0].min()
+    t1 = st[nph - 1][took[nph - 1]][:, 4].max()
+    log(f"timeline of one launch ({nph} phases, {st.shape[1]} workgroups): {t1 - t0:.1f} us from the first wait to the last flag")
+    kinds = ["q|k|v", "o", "gate|up", "down"]
+    rows = {k: [] for k in kinds}
+    for p in range(4, 4 * L):
+        cur, prv = st[p][took[p]], st[p - 1][took[p - 1]]
+        rows[kinds[p % 4]].append((prv[:, 3].max() - prv[:, 3].min(), (prv[:, 4] - prv[:, 3]).mean(),
+                                   (cur[:, 1] - prv[:, 4].max()).mean(), (cur[:, 2] - cur[:, 1]).mean(),
+                                   (cur[:, 3] - cur[:, 2]).mean(), (cur[:, 3] - cur[:, 2]).min(),
+                                   (cur[:, 3] - cur[:, 2]).max(), cur[:, 3].max() - prv[:, 3].max()))
+    log("  phase     spread    ack  detect   stage  stream (min .. max)   period   [us, mean over layers 2.." + str(L) + "]")
+    tot = 0.0
+    for k in kinds:
+        a = np.mean(np.array(rows[k]), axis=0)
+        tot += a[7]
+        log(f"  {k:8s} {a[0]:7.2f} {a[1]:6.2f} {a[2]:7.2f} {a[3]:7.2f} {a[4]:7.2f} ({a[5]:5.2f} .. {a[6]:5.2f}) {a[7]:8.2f}")
+    head = st[nph - 1][took[nph - 1]]
+    prv = st[nph - 2][took[nph - 2]]
+    log(f"  one layer: {tot:.2f} us; vocabulary phase: stage {np.mean(head[:, 2] - head[:, 1]):.2f} us, stream "
+        f"{np.mean(head[:, 3] - head[:, 2]):.1f} us ({(head[:, 3] - head[:, 2]).min():.1f} .. {(head[:, 3] - head[:, 2]).max():.1f}), "
+        f"period {head[:, 3].max() - prv[:, 3].max():.1f} us")
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -36,6 +78,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--m", type=int, default=8, help="candidate positions per step (gamma + 1)")
     ap.add_argument("--layers", type=int, default=None, help="override the layer count (debug only)")
+    ap.add_argument("--model", choices=("8b", "32b"), default="8b", help="layer shapes: Qwen3-8B (36 layers, the "
+                    "headline workload) or Qwen3-32B (64 layers; an extra line, not the headline)")
     ap.add_argument("--detail", action="store_true", help="also time every linear shape cold, the bf16 twin step "
                     "and the pure read stream (stderr)")
     ap.add_argument("--detail32", action="store_true", help="also time the Qwen3-32B layer shapes cold at "
@@ -48,6 +92,8 @@ def main() -> int:
     ap.add_argument("--calibrate", action="store_true", help="also run the plain copy kernel over 1 GiB (reference "
                     "for scaling hardware byte counters in rocprofv3 --pmc runs)")
     ap.add_argument("--no-twin", action="store_true", help="skip the bf16-weight twin of the step")
+    ap.add_argument("--timeline", action="store_true", help="also run one step with per-phase time stamps "
+                    "(quasar_sequence_run_stamped) and print where the time of a phase goes (stderr)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the library has no multi-GPU path); "
@@ -65,10 +111,15 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     M = args.m
-    L = args.layers or synth.QWEN3_8B_LAYERS
-    H = synth.QWEN3_8B_HIDDEN
+    big = args.model == "32b"
+    if big and (args.detail or args.detail_layer or args.detail4):
+        print("bench.py: the --detail* sections are written for the 8B shapes", file=sys.stderr)
+        return 2
+    L = args.layers or (synth.QWEN3_32B_LAYERS if big else synth.QWEN3_8B_LAYERS)
+    H = 5120 if big else synth.QWEN3_8B_HIDDEN
     V = synth.QWEN3_VOCAB
-    shapes = synth.QWEN3_8B_LAYER
+    shapes = synth.QWEN3_32B_LAYER if big else synth.QWEN3_8B_LAYER
+    width = {name: N for name, K, N in shapes}
     gen = torch.Generator(device=dev)
 
     # ------------------------------------------------------------- resident weights
@@ -79,7 +130,8 @@ def main() -> int:
         lin = []
         for i, (name, K, N) in enumerate(shapes):
             gen.manual_seed(synth.seed_for(4, li, i))
-            w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+            # (the 64-layer chain of the larger model overflows bf16 with std 0.02: unit gain there)
+            w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * (K ** -0.5 if big else 0.02)
             wq, sc = qb.quantize_weights(w)
             wp = qb.pack_bf16_weights(w) if twin else None
             lin.append((name, K, N, wq, sc, wp))
@@ -101,8 +153,8 @@ def main() -> int:
     # output, gate/up read o's, down reads gate's, the next layer reads down's
     def new(n):
         return torch.empty((M, n), dtype=torch.bfloat16, device=dev)
-    bufs = [{"q": new(4096), "k": new(1024), "v": new(1024), "o": new(4096), "g": new(12288), "u": new(12288),
-             "d": new(H)} for _ in range(L)]
+    bufs = [{"q": new(width["q_proj"]), "k": new(width["k_proj"]), "v": new(width["v_proj"]), "o": new(width["o_proj"]),
+             "g": new(width["gate_proj"]), "u": new(width["up_proj"]), "d": new(H)} for _ in range(L)]
     torch.cuda.synchronize()
     log(f"setup: {L} layers + LM head resident in {time.time() - t_setup:.1f} s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
@@ -240,8 +292,10 @@ def main() -> int:
 
     # The same weights with every linear reading a resident input instead of its predecessor's
     # output (no phase waits for another): what the weight stream alone sustains.
-    fixed_in = {4096: h0, 12288: torch.randn((M, 12288), generator=gen, device=dev, dtype=torch.float32)
-                .to(torch.bfloat16)}
+    fixed_in = {H: h0}
+    for _, K, _ in shapes:
+        if K not in fixed_in:
+            fixed_in[K] = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
     lin_free = []
     for li, lin in enumerate(layers):
         for name, K, N, wq, sc, wp in lin:
@@ -262,6 +316,9 @@ def main() -> int:
     log(f"W8A8 step (one persistent launch, {seq88.nphases} phases): {us_w8a8:.1f} us -> "
         f"{step_bytes[1] / us_w8a8 / 1e3:.1f} GB/s")
     del seq88
+
+    if args.timeline:
+        timeline_summary(seq8, L, log, np, torch)
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -471,6 +528,24 @@ def main() -> int:
     detail["drafter_us_per_proposal"] = t_prop * 1e6
     detail["drafter_ns_per_appended_token"] = t_app * 1e9
     drafter.close()
+
+    # Throughput model of Sec. 3.4, Eq. 13: S = (gamma * alpha + 1) / (T_draft + T_verify), tokens per unit time.
+    # T_draft and T_verify are this run's measurements (drafter proposal on the host; the verification weight
+    # stream of one step, attention excluded); gamma * alpha + 1, the tokens gained per step, is not something
+    # synthetic weights can give - the paper's reported mean acceptance lengths on Qwen3 at T = 0 (Table 1:
+    # 1.40 with the quantised verifier, 1.33 with the BF16 n-gram baseline) are put in as stated parameters.
+    eq13 = {"gamma": M - 1, "tokens_per_step_quantised_verifier": 1.40, "tokens_per_step_bf16_verifier": 1.33,
+            "acceptance_lengths_from": "paper, Table 1, Qwen3, T=0 (not measurable on random weights)",
+            "t_draft_us": t_prop * 1e6, "t_verify_int8_us": us_step,
+            "S_int8_tokens_per_s": 1.40 / ((t_prop * 1e6 + us_step) * 1e-6)}
+    if us_twin is not None:
+        eq13["t_verify_bf16_us"] = us_twin
+        eq13["S_bf16_tokens_per_s"] = 1.33 / ((t_prop * 1e6 + us_twin) * 1e-6)
+        eq13["S_ratio_int8_over_bf16"] = eq13["S_int8_tokens_per_s"] / eq13["S_bf16_tokens_per_s"]
+        log(f"Eq. 13 with the paper's acceptance lengths: S = {eq13['S_int8_tokens_per_s']:.0f} tokens/s (int8 verify) "
+            f"against {eq13['S_bf16_tokens_per_s']:.0f} tokens/s (bf16 verify): {eq13['S_ratio_int8_over_bf16']:.2f}x "
+            f"(weight stream only)")
+    detail["eq13"] = eq13
 
     if args.detail_layer:
         # A decoder block minus attention as four fused calls, chained through all 36 layers' own weights
@@ -734,13 +809,17 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "bf16 (int8 weight codes converted exactly to bf16 in registers, bf16 matrix cores, fp32 accumulate)",
         "data": "synthetic",
-        "config": {"workload": f"Qwen3-8B-shaped verification weight stream: {L} layers x 7 int8 linears + fused "
+        "config": {"workload": f"Qwen3-{'32B' if big else '8B'}-shaped verification weight stream: {L} layers x 7 int8 linears + fused "
                                f"LM head (V={V}) with greedy acceptance, M={M}, attention excluded",
                    "weight_bytes_per_step": weight_bytes, "algorithmic_bytes_per_step": step_bytes[1]},
         "hbm_gbps_step": step_bytes[1] / us_step / 1e3,
         "hbm_frac_step": step_bytes[1] / us_step / 1e3 / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "stream_sequence_kernel<8, int8> (whole step, one launch)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": f"stream_sequence_kernel<{8 if M <= 8 else (16 if M <= 16 else 32)}, int8> (whole step, one launch)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "traffic_source": None if traffic is None else
+                     "read from profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE of this kernel on "
+                     "this workload, scaled by the copy kernel's readings, from the profiling runs described in "
+                     "profiles/hbm_traffic_stream_sequence_kernel.md; not measured by this run",
                      "bytes_per_launch": avg_b, "us_per_launch": avg_us},
         "cpu_baseline": cpu,
         "paper_context": "Quasar reports 1.28x end-to-end over vanilla autoregressive decoding (1.18x for BF16-verify "
