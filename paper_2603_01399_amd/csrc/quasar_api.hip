@@ -907,13 +907,29 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     }
 
     int xs_max = 0, sc_max = 0, acc_max = 0;
-    for (SeqPhase &p : phases) {
+    std::vector<int> xs_of(phases.size());
+    for (size_t i = 0; i < phases.size(); ++i) {
+        SeqPhase &p = phases[i];
         if ((long long)p.T * (G + 1) >= (1ll << 31)) return QUASAR_ERR_SHAPE;   // the kernel splits tiles in 32 bits
         int xs, sc, ac;
         plan_phase(p, MP, w16, a8, G, xs, sc, ac);
+        xs_of[i] = xs;
+        p.raw_off = 0;
         if (xs > xs_max) xs_max = xs;
         if (sc > sc_max) sc_max = sc;
         if (ac > acc_max) acc_max = ac;
+    }
+    if (a8) {
+        // W8A8: a phase whose activations take one chunk and need no cache-bypassing reads parks them in LDS
+        // as bf16 (twice the bytes of its codes, behind them) and scans and quantises them there - one trip to
+        // memory on the hand-over path instead of two.  The activation region grows to three times such a
+        // phase's codes where the rest of the LDS allows it; phases that still do not fit read memory twice.
+        const int xs_cap = kMaxLds - (sc_max + 2 * kSeqWaves * NB * 1024 + acc_max);
+        auto eligible = [&](size_t i) { return phases[i].C == 1 && phases[i].wait != SEQ_WAIT_BARRIER; };
+        for (size_t i = 0; i < phases.size(); ++i)
+            if (eligible(i) && 3 * xs_of[i] <= xs_cap && 3 * xs_of[i] > xs_max) xs_max = 3 * xs_of[i];
+        for (size_t i = 0; i < phases.size(); ++i)
+            if (eligible(i) && 3 * xs_of[i] <= xs_max) phases[i].raw_off = xs_of[i];
     }
     // One workgroup of 16 waves per compute unit, or two alternating ones of 8.  Measured on the 36-layer
     // step: the alternating form is ~15% faster when the phases do not wait for each other (while one

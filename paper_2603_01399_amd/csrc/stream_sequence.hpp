@@ -58,7 +58,8 @@ struct SeqPhase {
     int V;
     int producer[2];         // SEQ_WAIT_FLAGS: phases whose completion flags gate this input (-1: unused)
     int publish;             // a later phase waits for this phase's flags
-    int pad_;
+    int raw_off;             // W8A8 form: LDS byte offset where the phase's bf16 activations are parked while they
+                             // are scanned and quantised out of LDS (0: they are read from memory twice instead)
     const float *smooth;     // W8A8: per-channel smoothing factors of the input ([K], nullptr: none)
     long long pad2_;
 };
@@ -367,27 +368,30 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     // have been cached before it was last written: barrier-ordered, reused buffers); otherwise
     // the 32 compute units of an XCD share one fetch of the activations through their L2.
     [[maybe_unused]] const unsigned int lds_base = lds_address_of(lds);
+    // bf16 activations, columns k0 .. of all tokens, straight into LDS at byte offset `dst` as 16-byte pieces
+    // [k/8][token]: 64 pieces (1 KB of LDS) per instruction - lane l fetches token l % MP (rows past M repeat
+    // row M - 1: their results are never used), 8 columns at 8 * (l / MP); waves take turns
+    auto x_direct = [&](const auto &P, long long k0, int npieces, unsigned int dst) {
+        const unsigned int x_voff = (unsigned int)min(lane & (MP - 1), M - 1) * (unsigned int)P.ldx * 2u +
+                                    16u * (unsigned int)(lane >> LMP);
+        const unsigned long long x0 = reinterpret_cast<unsigned long long>(P.x) + 2ull * (unsigned long long)k0;
+        const int ninstr = (npieces + 63) >> 6;
+        for (int i = w; i < ninstr; i += NW) {
+            const unsigned long long gb = x0 + (unsigned long long)i * (unsigned long long)(1024 / MP);
+            const unsigned int glo = __builtin_amdgcn_readfirstlane((unsigned int)gb);
+            const unsigned int ghi = __builtin_amdgcn_readfirstlane((unsigned int)(gb >> 32));
+            const unsigned long long gbase = ((unsigned long long)ghi << 32) | glo;
+            const unsigned int laddr = lds_base + dst + (unsigned int)i * 1024u;
+            if (i * 64 + 64 <= npieces) load_to_lds_16(gbase, x_voff, laddr);
+            else if (i * 64 + lane < npieces) load_to_lds_16(gbase, x_voff, laddr);
+        }
+    };
     auto x_stage = [&](const auto &P, int c, bool coherent) {
         const int scc = min(P.SC, P.S - c * P.SC);
         const int npieces = scc * PPS * MP;
         if constexpr (!A8) {
             if (!coherent) {
-                // 64 pieces (1 KB of LDS) per instruction: lane l fetches token l % MP (rows past M repeat
-                // row M - 1: their results are never used), 8 columns at 8 * (l / MP); waves take turns
-                const unsigned int x_voff = (unsigned int)min(lane & (MP - 1), M - 1) * (unsigned int)P.ldx * 2u +
-                                            16u * (unsigned int)(lane >> LMP);
-                const unsigned long long x0 = reinterpret_cast<unsigned long long>(P.x) +
-                                              2ull * (unsigned long long)c * P.SC * KSTEP;
-                const int ninstr = (npieces + 63) >> 6;
-                for (int i = w; i < ninstr; i += NW) {
-                    const unsigned long long gb = x0 + (unsigned long long)i * (unsigned long long)(1024 / MP);
-                    const unsigned int glo = __builtin_amdgcn_readfirstlane((unsigned int)gb);
-                    const unsigned int ghi = __builtin_amdgcn_readfirstlane((unsigned int)(gb >> 32));
-                    const unsigned long long gbase = ((unsigned long long)ghi << 32) | glo;
-                    const unsigned int laddr = lds_base + (unsigned int)i * 1024u;
-                    if (i * 64 + 64 <= npieces) load_to_lds_16(gbase, x_voff, laddr);
-                    else if (i * 64 + lane < npieces) load_to_lds_16(gbase, x_voff, laddr);
-                }
+                x_direct(P, (long long)c * P.SC * KSTEP, npieces, 0u);
                 return;
             }
         }
@@ -418,7 +422,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     // hits the caches.
     const int m_own = tid & (MP - 1);
     float a8_inv = 0.f;
-    constexpr int AXB = 4;       // pieces per thread and batch (= all of x at K = 4096, M <= 8)
+    constexpr int AXB = 3;       // pieces per thread and batch (four would spill)
     auto a8_load = [&](const auto &P, long long k, bool coherent) -> u32x4 {
         if (coherent) return coherent_load_u32x4(P.x + m_own * P.ldx + k);
         return *as_global(reinterpret_cast<const u32x4 *>(P.x + m_own * P.ldx + k));
@@ -498,6 +502,38 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
             }
         }
     };
+    // The same two passes out of LDS (a phase with raw_off != 0: one K chunk, its bf16 activations parked at
+    // raw_off by x_direct): one trip to memory instead of two, and the trip needs no registers.
+    auto x_scan_quant_lds = [&](const auto &P) {
+        if (tid < 32) tok_amax[tid] = 0u;
+        lds_barrier();            // (also: the parked activations have landed - the caller waited for its loads)
+        const int npieces = (P.K / 8) * MP;
+        const u32x4 *raw = reinterpret_cast<const u32x4 *>(lds + P.raw_off);
+        if (m_own < M) {
+            float amax = 0.f;
+            for (int idx = tid; idx < npieces; idx += nthreads) {
+                float xt[8];
+                a8_smooth(P, raw[idx], 8ll * (idx >> LMP), xt);
+                amax = fmaxf(amax, piece_amax(xt));
+            }
+            __hip_atomic_fetch_max(&tok_amax[m_own], __float_as_uint(amax), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        lds_barrier();
+        const float amax_own = __uint_as_float(tok_amax[m_own]);
+        a8_inv = inverse_step_of(amax_own);
+        if (tid < MP) tok_dx[tid] = step_of(amax_own);
+        for (int idx = tid; idx < npieces; idx += nthreads) {
+            const int p8 = idx >> LMP;
+            u32x2 codes = {0u, 0u};
+            if (m_own < M) {
+                float xt[8];
+                a8_smooth(P, raw[idx], 8ll * p8, xt);
+                codes = quantize_piece(xt, a8_inv);
+            }
+            *reinterpret_cast<u32x2 *>(lds + (((p8 >> 1) * MP + m_own) * 16 + 8 * (p8 & 1))) = codes;
+        }
+    };
     // wait (wave 0 polls, four flags per lane and round trip) until every workgroup has raised
     // its flag for phase `pp` in this launch
     auto flags_wait = [&](int pp) {
@@ -532,6 +568,27 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
                 const long long n = (long long)(t - P.seg[s].tile_begin) * kTileRows + (i & 15);
                 reinterpret_cast<unsigned int *>(sc_lds)[i >> 1] =
                     *as_global(reinterpret_cast<const unsigned int *>(P.seg[s].scales + n));
+            }
+        }
+    };
+    // The same in one load of two scales per thread, which covers all but huge shares (else scale_stage): the
+    // member matrix of a thread's row is picked among values held in scalar registers - looking it up in the
+    // phase table per lane, as scale_stage does, costs a round trip of its own before the load can be issued.
+    auto scale_stage_one_trip = [&](const auto &P, int t0, int ntiles) {
+        if constexpr (!W16) {
+            if (ntiles * (kTileRows / 2) <= nthreads) {
+                if (tid < ntiles * (kTileRows / 2)) {
+                    const int t = t0 + (tid >> 3);
+                    const uint16_t *base = P.seg[0].scales;
+                    int tb = 0;
+                    if (P.nseg > 1 && t >= P.seg[1].tile_begin) { base = P.seg[1].scales; tb = P.seg[1].tile_begin; }
+                    if (P.nseg > 2 && t >= P.seg[2].tile_begin) { base = P.seg[2].scales; tb = P.seg[2].tile_begin; }
+                    if (P.nseg > 3 && t >= P.seg[3].tile_begin) { base = P.seg[3].scales; tb = P.seg[3].tile_begin; }
+                    reinterpret_cast<unsigned int *>(sc_lds)[tid] = *as_global(reinterpret_cast<const unsigned int *>(
+                        base + (long long)(t - tb) * kTileRows + ((2 * tid) & 15)));
+                }
+            } else {
+                scale_stage(P, t0, ntiles);
             }
         }
     };
@@ -662,8 +719,18 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
                     c_leave();
                     continue;
                 }
-                if constexpr (A8) scale_stage(P, c_t0, c_ntiles);
-                if constexpr (A8) x_scan(P, P.wait == SEQ_WAIT_BARRIER);
+                if constexpr (A8) {
+                    if (P.raw_off != 0) {
+                        // scales and activations are requested together; everything is waited for once
+                        x_direct(P, 0, (P.K / 8) * MP, (unsigned int)P.raw_off);
+                        scale_stage_one_trip(P, c_t0, c_ntiles);
+                        __builtin_amdgcn_s_waitcnt(0x0F70);
+                        x_scan_quant_lds(P);
+                    } else {
+                        scale_stage_one_trip(P, c_t0, c_ntiles);
+                        x_scan(P, P.wait == SEQ_WAIT_BARRIER);
+                    }
+                }
             }
             const int scc = min(P.SC, P.S - c_c * P.SC);
             const int s_lo = (scc * w) / NW;
@@ -683,32 +750,13 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
             nocomp = false;
             c_reseg();
             if constexpr (A8) {
-                x_quant(P, c_c, P.wait == SEQ_WAIT_BARRIER);
+                if (P.raw_off == 0) x_quant(P, c_c, P.wait == SEQ_WAIT_BARRIER);
             } else {
                 // activations and row scales are requested together and waited for once: one round trip,
                 // not two (the activations first: they go straight to LDS, so no loaded value is held across
-                // their issue loop).  One load of two scales per thread covers the scales in all but huge
-                // shares; the member matrix of a thread's row is picked among values held in scalar
-                // registers - looking it up in the phase table per lane would cost a round trip of its own.
+                // their issue loop)
                 x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
-                if constexpr (!W16) {
-                    if (c_c == 0) {
-                        if (c_ntiles * (kTileRows / 2) <= nthreads) {
-                            if (tid < c_ntiles * (kTileRows / 2)) {
-                                const int t = c_t0 + (tid >> 3);
-                                const uint16_t *base = P.seg[0].scales;
-                                int tb = 0;
-                                if (P.nseg > 1 && t >= P.seg[1].tile_begin) { base = P.seg[1].scales; tb = P.seg[1].tile_begin; }
-                                if (P.nseg > 2 && t >= P.seg[2].tile_begin) { base = P.seg[2].scales; tb = P.seg[2].tile_begin; }
-                                if (P.nseg > 3 && t >= P.seg[3].tile_begin) { base = P.seg[3].scales; tb = P.seg[3].tile_begin; }
-                                reinterpret_cast<unsigned int *>(sc_lds)[tid] = *as_global(reinterpret_cast<const unsigned int *>(
-                                    base + (long long)(t - tb) * kTileRows + ((2 * tid) & 15)));
-                            }
-                        } else {
-                            scale_stage(P, c_t0, c_ntiles);
-                        }
-                    }
-                }
+                if (c_c == 0) scale_stage_one_trip(P, c_t0, c_ntiles);
             }
             // known-empty load queue: keeps the counted waits of the ring exact (see stream_gemm.hpp)
             __builtin_amdgcn_s_waitcnt(0x0F70);
