@@ -518,7 +518,7 @@ def main() -> int:
     t_app = (time.perf_counter() - t0) / ctx.size
     lib, hnd = qb.lib(), drafter._h
     import ctypes
-    buf, nd, kk = (ctypes.c_int32 * 8)(), ctypes.c_int64(0), ctypes.c_int(0)
+    buf, nd, kk = (ctypes.c_int32 * max(8, M))(), ctypes.c_int64(0), ctypes.c_int(0)
     t0 = time.perf_counter()
     for _ in range(2000):
         lib.quasar_drafter_propose(hnd, M - 1, buf, ctypes.byref(nd), ctypes.byref(kk))

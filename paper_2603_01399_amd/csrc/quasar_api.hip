@@ -906,31 +906,36 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
         if (p.producer[1] >= 0) phases[p.producer[1]].publish = 1;
     }
 
-    int xs_max = 0, sc_max = 0, acc_max = 0;
-    std::vector<int> xs_of(phases.size());
+    // LDS of a phase: activations (a K chunk), row scales, the cross-wave staging area, per-tile running sums
+    // when K is chunked.  Every phase lays the LDS out for itself; the launch reserves the largest total.
+    std::vector<int> acc_of(phases.size());
+    const int stage1 = 2 * kSeqWaves * NB * 1024, stage2 = kSeqWaves2 * NB * 1024;
     for (size_t i = 0; i < phases.size(); ++i) {
         SeqPhase &p = phases[i];
         if ((long long)p.T * (G + 1) >= (1ll << 31)) return QUASAR_ERR_SHAPE;   // the kernel splits tiles in 32 bits
         int xs, sc, ac;
         plan_phase(p, MP, w16, a8, G, xs, sc, ac);
-        xs_of[i] = xs;
+        p.xs_bytes = xs;
+        p.sc_bytes = sc;
         p.raw_off = 0;
-        if (xs > xs_max) xs_max = xs;
-        if (sc > sc_max) sc_max = sc;
-        if (ac > acc_max) acc_max = ac;
-    }
-    if (a8) {
+        acc_of[i] = ac;
+        if (xs + sc + stage1 + ac > kMaxLds) return QUASAR_ERR_SHAPE;
         // W8A8: a phase whose activations take one chunk and need no cache-bypassing reads parks them in LDS
         // as bf16 (twice the bytes of its codes, behind them) and scans and quantises them there - one trip to
-        // memory on the hand-over path instead of two.  The activation region grows to three times such a
-        // phase's codes where the rest of the LDS allows it; phases that still do not fit read memory twice.
-        const int xs_cap = kMaxLds - (sc_max + 2 * kSeqWaves * NB * 1024 + acc_max);
-        auto eligible = [&](size_t i) { return phases[i].C == 1 && phases[i].wait != SEQ_WAIT_BARRIER; };
-        for (size_t i = 0; i < phases.size(); ++i)
-            if (eligible(i) && 3 * xs_of[i] <= xs_cap && 3 * xs_of[i] > xs_max) xs_max = 3 * xs_of[i];
-        for (size_t i = 0; i < phases.size(); ++i)
-            if (eligible(i) && 3 * xs_of[i] <= xs_max) phases[i].raw_off = xs_of[i];
+        // memory on the hand-over path instead of two - if the LDS has room for that.
+        if (a8 && p.C == 1 && p.wait != SEQ_WAIT_BARRIER && 3 * xs + sc + stage1 + ac <= kMaxLds) {
+            p.raw_off = xs;
+            p.xs_bytes = 3 * xs;
+        }
     }
+    auto lds_need = [&](int stage_bytes) {
+        int most = 0;
+        for (size_t i = 0; i < phases.size(); ++i) {
+            const int n = phases[i].xs_bytes + phases[i].sc_bytes + stage_bytes + acc_of[i];
+            if (n > most) most = n;
+        }
+        return most;
+    };
     // One workgroup of 16 waves per compute unit, or two alternating ones of 8.  Measured on the 36-layer
     // step: the alternating form is ~15% faster when the phases do not wait for each other (while one
     // workgroup stages its activations the other streams) and ~25% slower on a chain of dependent phases
@@ -943,9 +948,9 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     const int form = g_seq_form.load();
     const bool want2 = form == 2 || (form == 0 && 4 * n_waits <= (int)phases.size() && phases.size() >= 2);
     int roles = 1;
-    int lds = xs_max + sc_max + 2 * kSeqWaves * NB * 1024 + acc_max;
+    int lds = lds_need(stage1);
     if (MP == 8 && want2) {
-        int lds2 = xs_max + sc_max + kSeqWaves2 * NB * 1024 + acc_max;
+        int lds2 = lds_need(stage2);
         if (lds2 < kSeqMinLds2) lds2 = kSeqMinLds2;
         if (lds2 <= kSeqMaxLds2 && sequence_residency_of<2>(MP, w16, a8, lds2) >= 2) {
             roles = 2;
@@ -967,7 +972,8 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     if (hipDeviceSynchronize() != hipSuccess) return QUASAR_ERR_HIP;
     SeqHandle h{};
     h.magic = kSeqMagic; h.nphases = (int)phases.size(); h.M = (int)M; h.MP = MP; h.w16 = w16 ? 1 : 0;
-    h.xs_bytes = xs_max; h.sc_bytes = sc_max; h.lds_bytes = (roles == 1 && lds < kMinLds) ? kMinLds : lds;
+    h.xs_bytes = 0; h.sc_bytes = 256;      // layout before the first phase (the kernel's start-up scratch sits in the staging area)
+    h.lds_bytes = (roles == 1 && lds < kMinLds) ? kMinLds : lds;
     h.grid = G * roles; h.roles = roles;
     h.has_verify = verify ? 1 : 0; h.n_linears = (int)n_linears; h.a8 = a8 ? 1 : 0;
     h.n_barriers = 0; h.n_flag_waits = 0;

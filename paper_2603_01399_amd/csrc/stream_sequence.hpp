@@ -61,7 +61,8 @@ struct SeqPhase {
     int raw_off;             // W8A8 form: LDS byte offset where the phase's bf16 activations are parked while they
                              // are scanned and quantised out of LDS (0: they are read from memory twice instead)
     const float *smooth;     // W8A8: per-channel smoothing factors of the input ([K], nullptr: none)
-    long long pad2_;
+    int xs_bytes;            // LDS bytes this phase reserves for activations (a chunk; W8A8: codes, and the parked bf16)
+    int sc_bytes;            // LDS bytes for its row scales (+ 256 for the per-token step sizes of the W8A8 form)
 };
 
 typedef const __attribute__((address_space(4))) SeqPhase *const_phase_ptr;   // scalar (constant) loads
@@ -77,8 +78,8 @@ struct SeqParams {
     const SeqPhase *phases;  // device memory, never written while the kernel runs
     int nphases;
     int M;
-    int xs_bytes;            // LDS reserved for activations (max over phases)
-    int sc_bytes;            // LDS reserved for row scales (max over phases)
+    int xs_bytes;            // LDS layout before the first phase (each phase then lays the LDS out for itself:
+    int sc_bytes;            // activations, scales, cross-wave staging, per-tile sums, in that order)
     unsigned int *sync;      // [0] arrival counter, [1] error flag (both zero at launch), [2] launch epoch,
                              // [8], [9] members of role 0 / 1 so far, [64 + id] workgroups seen on compute unit id
     unsigned int *flags;     // [nphases][gridDim.x]: epoch of the launch in which the workgroup finished the phase
@@ -196,12 +197,20 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     const const_phase_ptr phases = (const_phase_ptr)(unsigned long long)sp.phases;
 
     u32x4 *xs = reinterpret_cast<u32x4 *>(lds);
+    // regions behind the activations; moved at every phase entry to that phase's own sizes
     uint16_t *sc_lds = reinterpret_cast<uint16_t *>(lds + sp.xs_bytes);
     // the last 256 bytes of the scale region: per-token step sizes and maxima of the W8A8 form
     float *tok_dx = reinterpret_cast<float *>(lds + sp.xs_bytes + sp.sc_bytes - 256);                  // [32]
     unsigned int *tok_amax = reinterpret_cast<unsigned int *>(lds + sp.xs_bytes + sp.sc_bytes - 128);  // [32]
     f32x4 *stage = reinterpret_cast<f32x4 *>(lds + sp.xs_bytes + sp.sc_bytes);   // [2][NW][NB][64]
     f32x4 *accs = stage + NPAR * NW * NB * 64;                                   // [ntiles][NB][64] (C > 1)
+    auto lay_out = [&](int xs, int sc) {
+        sc_lds = reinterpret_cast<uint16_t *>(lds + xs);
+        tok_dx = reinterpret_cast<float *>(lds + xs + sc - 256);
+        tok_amax = reinterpret_cast<unsigned int *>(lds + xs + sc - 128);
+        stage = reinterpret_cast<f32x4 *>(lds + xs + sc);
+        accs = stage + NPAR * NW * NB * 64;
+    };
 
     // role (which phases) and rank (which tiles) of this workgroup
     int role = 0, rk = b;
@@ -705,6 +714,9 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
                     ++c_ph;
                     continue;
                 }
+                // (this wave has finished everything of the previous phase, its last epilogue included; what the
+                // other waves still read of the old layout is read before they pass the barrier below)
+                lay_out(P.xs_bytes, P.sc_bytes);
                 stamp(c_ph, 0);
                 if (P.wait != SEQ_WAIT_BARRIER) {
                     if (P.wait == SEQ_WAIT_FLAGS) {
