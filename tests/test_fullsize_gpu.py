@@ -309,3 +309,78 @@ def test_whole_step_launch_at_benchmark_size(qb):
             q_ref, s_ref = host[(li, name)]
             assert np.array_equal(bf16_to_host(bufs8[li][name]), a8.w8a8_linear(xin[name], q_ref, s_ref)), (li, name)
     print("W8A8 form identical to its single calls and to the oracle on the checked layers", flush=True)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("M", [8, 16])
+def test_whole_step_launch_with_qwen3_32b_layer_shapes(qb, M):
+    """Two decoder layers of the larger model's shapes (hidden 5120, q 8192 wide, K up to 25600: every
+    phase's activations take several LDS chunks from M = 16 on) and a vocabulary phase, in one launch:
+    all outputs, the argmax and the accepted length equal the single calls bit for bit, and the last
+    layer's outputs are within the tolerance of the oracle applied to the inputs that layer consumed."""
+    print("32B-shaped whole step, M", M, flush=True)
+    shapes = synth.QWEN3_32B_LAYER
+    H, V, L = 5120, 4096, 2
+    dev = torch.device("cuda")
+    layers, host = [], {}
+    for li in range(L):
+        lin = []
+        for i, (name, K, N) in enumerate(shapes):
+            w = synth.normal_weights(N, K, seed=synth.seed_for(13, li, i), std=1.0 / np.sqrt(K))
+            wq, sc = qb.quantize_weights(f32_to_dev(w))
+            if li == L - 1:
+                q_ref, s_ref = ref.quantize_weights(w)
+                assert np.array_equal(bf16_to_host(sc), s_ref), name
+                assert np.array_equal(qb.unpack_weights(wq, N, K).cpu().numpy(), q_ref), name
+                host[name] = (q_ref, s_ref)
+            del w
+            lin.append((name, K, N, wq, sc))
+        layers.append(lin)
+    wv = synth.normal_weights(V, H, seed=synth.seed_for(13, 99, 1))
+    head_q, head_s = qb.quantize_weights(f32_to_dev(wv))
+    del wv
+    x0 = bf16_to_dev(synth.activations_bf16(M, H, seed=synth.seed_for(13, 99, M)))
+    draft = i32_to_dev(np.arange(1, M, dtype=np.int32))
+
+    def buffers():
+        return [{n: torch.zeros((M, N), dtype=torch.bfloat16, device=dev) for n, _, N in shapes} for _ in range(L)]
+
+    def linears(bufs):
+        lst = []
+        for li, lin in enumerate(layers):
+            hin = x0 if li == 0 else bufs[li - 1]["down_proj"]
+            b = bufs[li]
+            src = {"q_proj": hin, "k_proj": hin, "v_proj": hin, "o_proj": b["q_proj"], "gate_proj": b["o_proj"],
+                   "up_proj": b["o_proj"], "down_proj": b["gate_proj"]}
+            for name, K, N, wq, sc in lin:
+                lst.append((src[name], wq, sc, N, b[name]))
+        return lst
+
+    bufs = buffers()
+    am = torch.full((M,), -1, dtype=torch.int32, device=dev)
+    acc = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    seq = qb.Sequence(linears(bufs), verify=(bufs[L - 1]["down_proj"], head_q, head_s, V, draft, am, acc))
+    assert seq.nphases == 4 * L + 1 and seq.n_barriers == 0
+    for _ in range(2):
+        seq.run()
+    torch.cuda.synchronize()
+    assert not seq.timed_out()
+    ref_bufs = buffers()
+    for x, wq, sc, N, y in linears(ref_bufs):
+        qb.w8_linear(x, wq, sc, N, y)
+    am2, acc2 = qb.lmhead_verify(ref_bufs[L - 1]["down_proj"], head_q, head_s, V, draft, qb.make_workspace(M, V, H))
+    torch.cuda.synchronize()
+    for li in range(L):
+        for name, _, _ in shapes:
+            assert torch.equal(bufs[li][name].view(torch.int16), ref_bufs[li][name].view(torch.int16)), (li, name)
+    assert torch.equal(am, am2) and torch.equal(acc, acc2)
+    li = L - 1
+    hin = bf16_to_host(bufs[li - 1]["down_proj"])
+    xin = {"q_proj": hin, "k_proj": hin, "v_proj": hin, "o_proj": bf16_to_host(bufs[li]["q_proj"]),
+           "gate_proj": bf16_to_host(bufs[li]["o_proj"]), "up_proj": bf16_to_host(bufs[li]["o_proj"]),
+           "down_proj": bf16_to_host(bufs[li]["gate_proj"])}
+    for name, K, N in shapes:
+        q_ref, s_ref = host[name]
+        err = ref.rel_maxabs_err(ref.bf16_bits_to_f64(bf16_to_host(bufs[li][name])), ref.w8_linear(xin[name], q_ref, s_ref))
+        print("32B layer", name, "M", M, "rel err", err, flush=True)
+        assert err <= TOL and err <= 4e-3
