@@ -404,10 +404,16 @@ def test_sequence_two_workgroups_per_compute_unit_same_bits(qb, M, hidden, kv, i
             assert took.any(axis=1).all()
             for a, b in ((0, 1), (1, 2), (2, 3), (3, 4)):
                 assert (stamps[:, :, a][took] <= stamps[:, :, b][took]).all(), (a, b)
-            # a phase's input was seen complete only after every producer had raised its flag
+            # gate|up reads all of o's output: its input was seen complete only after every workgroup with a
+            # share in o had summed its last tile.  (o and down read one member matrix of their producer phase
+            # - q of q|k|v, gate of gate|up - and wait for the workgroups that wrote that matrix only.)
+            for p in range(2, seq.nphases, 4):
+                if took[p].any() and took[p - 1].any():
+                    assert stamps[p, :, 1][took[p]].min() >= stamps[p - 1, :, 3][took[p - 1]].max()
+            # nobody saw an input complete before the first of its producers had raised its flag
             for p in range(1, seq.nphases):
                 if took[p].any() and took[p - 1].any() and p % 4 != 0:
-                    assert stamps[p, :, 1][took[p]].min() >= stamps[p - 1, :, 3][took[p - 1]].max()
+                    assert stamps[p, :, 1][took[p]].min() >= stamps[p - 1, :, 4][took[p - 1]].min()
     finally:
         qb.set_sequence_form(0)
     bufs2, h2 = gpu_buffers(layers, M, x0)
