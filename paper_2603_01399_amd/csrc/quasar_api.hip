@@ -533,7 +533,8 @@ bool plan_phase(SeqPhase &ph, int MP, bool w16, bool a8, int G, int &xs_bytes, i
     const int x_bytes_per_step = ((w16 || a8) ? 64 : 128) * MP;
     choose_chunks(ph.S, x_bytes_per_step, 2 * kSeqWaves * NB * 1024, ph.SC, ph.C);
     const int tpw = (ph.T + G - 1) / G;
-    xs_bytes = ph.SC * x_bytes_per_step;
+    // (bf16 activations lie in LDS as token rows 16 bytes further apart than their length)
+    xs_bytes = ph.SC * x_bytes_per_step + (a8 ? 0 : MP * 16);
     // row scales, then 256 bytes for the per-token step sizes of the W8A8 form
     sc_bytes = (w16 ? 0 : ((tpw * kTileRows * 2 + 15) / 16) * 16) + 256;
     acc_bytes = ph.C > 1 ? tpw * NB * 1024 : 0;
@@ -923,9 +924,9 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
         // W8A8: a phase whose activations take one chunk and need no cache-bypassing reads parks them in LDS
         // as bf16 (twice the bytes of its codes, behind them) and scans and quantises them there - one trip to
         // memory on the hand-over path instead of two - if the LDS has room for that.
-        if (a8 && p.C == 1 && p.wait != SEQ_WAIT_BARRIER && 3 * xs + sc + stage1 + ac <= kMaxLds) {
+        if (a8 && p.C == 1 && p.wait != SEQ_WAIT_BARRIER && 3 * xs + MP * 16 + sc + stage1 + ac <= kMaxLds) {
             p.raw_off = xs;
-            p.xs_bytes = 3 * xs;
+            p.xs_bytes = 3 * xs + MP * 16;   // (parked as token rows 16 bytes further apart than their length)
         }
     }
     auto lds_need = [&](int stage_bytes) {

@@ -371,39 +371,70 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     }
     const int xm = (MP == 8) ? (mcol & 7) : mcol;
     // this lane's B operand inside a step: 8-element piece (W16: g, else 2g and 2g + 1), token xm
-    const unsigned int xlane = (unsigned int)((((W16 || A8) ? g : 2 * g) * MP + xm) * 16);
+    // W8A8: codes as 16-byte pieces [k/16][token]; bf16 activations: token rows (see x_direct), the lane's offset
+    // then depends on the phase's row length and is set at its entry
+    unsigned int xlane = (unsigned int)((((W16 || A8) ? g : 2 * g) * MP + xm) * 16);
+    [[maybe_unused]] unsigned int xrow16 = 0;   // MP = 32: bytes from token m to token m + 16
 
     // stage one activation chunk.  `coherent` reads go past the L2 (needed when the buffer may
     // have been cached before it was last written: barrier-ordered, reused buffers); otherwise
     // the 32 compute units of an XCD share one fetch of the activations through their L2.
     [[maybe_unused]] const unsigned int lds_base = lds_address_of(lds);
-    // bf16 activations, columns k0 .. of all tokens, straight into LDS at byte offset `dst` as 16-byte pieces
-    // [k/8][token]: 64 pieces (1 KB of LDS) per instruction - lane l fetches token l % MP (rows past M repeat
-    // row M - 1: their results are never used), 8 columns at 8 * (l / MP); waves take turns
-    auto x_direct = [&](const auto &P, long long k0, int npieces, unsigned int dst) {
-        const unsigned int x_voff = (unsigned int)min(lane & (MP - 1), M - 1) * (unsigned int)P.ldx * 2u +
-                                    16u * (unsigned int)(lane >> LMP);
-        const unsigned long long x0 = reinterpret_cast<unsigned long long>(P.x) + 2ull * (unsigned long long)k0;
-        const int ninstr = (npieces + 63) >> 6;
-        for (int i = w; i < ninstr; i += NW) {
-            const unsigned long long gb = x0 + (unsigned long long)i * (unsigned long long)(1024 / MP);
+    // bf16 activations, columns k0 .. k0 + ncols - 1 of all tokens, straight into LDS at byte offset `dst`, one
+    // token after the other: token m at dst + m * rs (rs = row bytes + 16: the skew keeps the tokens of one column
+    // in different banks).  One instruction moves 1 KB that is contiguous in memory AND in LDS - measured on all
+    // 256 compute units fetching the same 64 KB: 100 GB/s per compute unit, against 35 GB/s when an instruction
+    // gathers 128 bytes from each of eight rows (rows are a multiple of 4 KB apart and meet in one cache channel).
+    // Rows past M repeat row M - 1: their results are never used.  Instruction j covers piece j % ipr of token
+    // j / ipr; wave w takes j = w, w + NW, ...
+    // The work is split in two: x_plan does the arithmetic (divisions included) and may run while the wave would
+    // otherwise idle in front of the phase's wait; x_issue then costs a dozen scalar instructions per load.  (On
+    // the hand-over path the sixteen waves of a workgroup execute this code side by side, four to a SIMD, and the
+    // youngest wave of a SIMD was found to reach its first load 1.5 us after the flags had been seen.)
+    struct XPlan {
+        unsigned long long x0, ld2;
+        unsigned int rs;
+        int m, i, dq, dr, ipr, count, rowbytes;
+    };
+    auto x_plan = [&](const auto &P, long long k0, int ncols, unsigned int rs) -> XPlan {
+        XPlan pl;
+        pl.rowbytes = ncols * 2;
+        pl.ipr = (pl.rowbytes + 1023) >> 10;
+        const int ninstr = pl.ipr * MP;
+        pl.m = w / pl.ipr;
+        pl.i = w - pl.m * pl.ipr;
+        pl.dq = NW / pl.ipr;
+        pl.dr = NW - pl.dq * pl.ipr;
+        pl.count = w < ninstr ? (ninstr - w + NW - 1) / NW : 0;
+        pl.x0 = reinterpret_cast<unsigned long long>(P.x) + 2ull * (unsigned long long)k0;
+        pl.ld2 = (unsigned long long)P.ldx * 2ull;
+        pl.rs = rs;
+        return pl;
+    };
+    auto x_issue = [&](const XPlan &pl, unsigned int dst) {
+        const unsigned int x_voff = (unsigned int)lane * 16u;
+        int m = pl.m, i = pl.i;
+        for (int n = 0; n < pl.count; ++n) {
+            const unsigned long long gb = pl.x0 + (unsigned long long)min(m, M - 1) * pl.ld2 + (unsigned long long)i * 1024ull;
             const unsigned int glo = __builtin_amdgcn_readfirstlane((unsigned int)gb);
             const unsigned int ghi = __builtin_amdgcn_readfirstlane((unsigned int)(gb >> 32));
             const unsigned long long gbase = ((unsigned long long)ghi << 32) | glo;
-            const unsigned int laddr = lds_base + dst + (unsigned int)i * 1024u;
-            if (i * 64 + 64 <= npieces) load_to_lds_16(gbase, x_voff, laddr);
-            else if (i * 64 + lane < npieces) load_to_lds_16(gbase, x_voff, laddr);
+            const unsigned int laddr = __builtin_amdgcn_readfirstlane(lds_base + dst + (unsigned int)m * pl.rs + (unsigned int)i * 1024u);
+            if (i * 1024 + 1024 <= pl.rowbytes) load_to_lds_16(gbase, x_voff, laddr);
+            else if (i * 1024 + lane * 16 < pl.rowbytes) load_to_lds_16(gbase, x_voff, laddr);
+            i += pl.dr;
+            m += pl.dq;
+            if (i >= pl.ipr) { i -= pl.ipr; ++m; }
         }
+    };
+    auto x_direct = [&](const auto &P, long long k0, int ncols, unsigned int dst, unsigned int rs) {
+        x_issue(x_plan(P, k0, ncols, rs), dst);
     };
     auto x_stage = [&](const auto &P, int c, bool coherent) {
         const int scc = min(P.SC, P.S - c * P.SC);
         const int npieces = scc * PPS * MP;
-        if constexpr (!A8) {
-            if (!coherent) {
-                x_direct(P, (long long)c * P.SC * KSTEP, npieces, 0u);
-                return;
-            }
-        }
+        const unsigned int rs = (unsigned int)(P.SC * KSTEP * 2 + 16);
+
         for (int base = 0; base < npieces; base += nthreads * XB) {
             u32x4 v[XB];
 #pragma unroll
@@ -422,7 +453,8 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
 #pragma unroll
             for (int i = 0; i < XB; ++i) {
                 const int idx = base + i * nthreads + tid;
-                if (idx < npieces) xs[idx] = v[i];
+                if (idx < npieces)
+                    *reinterpret_cast<u32x4 *>(lds + (unsigned int)(idx & (MP - 1)) * rs + (unsigned int)(idx >> LMP) * 16u) = v[i];
             }
         }
     };
@@ -517,12 +549,13 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
         if (tid < 32) tok_amax[tid] = 0u;
         lds_barrier();            // (also: the parked activations have landed - the caller waited for its loads)
         const int npieces = (P.K / 8) * MP;
-        const u32x4 *raw = reinterpret_cast<const u32x4 *>(lds + P.raw_off);
+        // this thread's token row of the parked activations (row bytes + 16 apart); piece p8 at 16 * p8
+        const unsigned char *raw = lds + P.raw_off + m_own * (P.K * 2 + 16);
         if (m_own < M) {
             float amax = 0.f;
             for (int idx = tid; idx < npieces; idx += nthreads) {
                 float xt[8];
-                a8_smooth(P, raw[idx], 8ll * (idx >> LMP), xt);
+                a8_smooth(P, *reinterpret_cast<const u32x4 *>(raw + (idx >> LMP) * 16), 8ll * (idx >> LMP), xt);
                 amax = fmaxf(amax, piece_amax(xt));
             }
             __hip_atomic_fetch_max(&tok_amax[m_own], __float_as_uint(amax), __ATOMIC_RELAXED,
@@ -537,7 +570,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
             u32x2 codes = {0u, 0u};
             if (m_own < M) {
                 float xt[8];
-                a8_smooth(P, raw[idx], 8ll * p8, xt);
+                a8_smooth(P, *reinterpret_cast<const u32x4 *>(raw + p8 * 16), 8ll * p8, xt);
                 codes = quantize_piece(xt, a8_inv);
             }
             *reinterpret_cast<u32x2 *>(lds + (((p8 >> 1) * MP + m_own) * 16 + 8 * (p8 & 1))) = codes;
@@ -583,22 +616,31 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     // The same in one load of two scales per thread, which covers all but huge shares (else scale_stage): the
     // member matrix of a thread's row is picked among values held in scalar registers - looking it up in the
     // phase table per lane, as scale_stage does, costs a round trip of its own before the load can be issued.
+    // (scale_fetch only requests pair `i` of the workgroup's row scales; scale_put stores what it returned)
+    auto scale_fetch = [&](const auto &P, int t0, int ntiles, int i) -> unsigned int {
+        unsigned int v = 0u;
+        if constexpr (!W16) {
+            if (i >= 0 && i < ntiles * (kTileRows / 2)) {
+                const int t = t0 + (i >> 3);
+                const uint16_t *base = P.seg[0].scales;
+                int tb = 0;
+                if (P.nseg > 1 && t >= P.seg[1].tile_begin) { base = P.seg[1].scales; tb = P.seg[1].tile_begin; }
+                if (P.nseg > 2 && t >= P.seg[2].tile_begin) { base = P.seg[2].scales; tb = P.seg[2].tile_begin; }
+                if (P.nseg > 3 && t >= P.seg[3].tile_begin) { base = P.seg[3].scales; tb = P.seg[3].tile_begin; }
+                v = *as_global(reinterpret_cast<const unsigned int *>(base + (long long)(t - tb) * kTileRows + ((2 * i) & 15)));
+            }
+        }
+        return v;
+    };
+    auto scale_put = [&](int ntiles, int i, unsigned int v) {
+        if constexpr (!W16) {
+            if (i >= 0 && i < ntiles * (kTileRows / 2)) reinterpret_cast<unsigned int *>(sc_lds)[i] = v;
+        }
+    };
     auto scale_stage_one_trip = [&](const auto &P, int t0, int ntiles) {
         if constexpr (!W16) {
-            if (ntiles * (kTileRows / 2) <= nthreads) {
-                if (tid < ntiles * (kTileRows / 2)) {
-                    const int t = t0 + (tid >> 3);
-                    const uint16_t *base = P.seg[0].scales;
-                    int tb = 0;
-                    if (P.nseg > 1 && t >= P.seg[1].tile_begin) { base = P.seg[1].scales; tb = P.seg[1].tile_begin; }
-                    if (P.nseg > 2 && t >= P.seg[2].tile_begin) { base = P.seg[2].scales; tb = P.seg[2].tile_begin; }
-                    if (P.nseg > 3 && t >= P.seg[3].tile_begin) { base = P.seg[3].scales; tb = P.seg[3].tile_begin; }
-                    reinterpret_cast<unsigned int *>(sc_lds)[tid] = *as_global(reinterpret_cast<const unsigned int *>(
-                        base + (long long)(t - tb) * kTileRows + ((2 * tid) & 15)));
-                }
-            } else {
-                scale_stage(P, t0, ntiles);
-            }
+            if (ntiles * (kTileRows / 2) <= nthreads) scale_put(ntiles, tid, scale_fetch(P, t0, ntiles, tid));
+            else scale_stage(P, t0, ntiles);
         }
     };
     bool stored = false;   // this wave has output stores in flight
@@ -685,6 +727,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
         }
     };
     bool nocomp = false;      // padding slots: no arithmetic
+    bool sc_early = false;    // the current phase's row scales were requested ahead of its wait
     int unit_left = 0;        // slots (padded) left in the current unit
     // the current (phase, chunk) is done
     auto c_leave = [&]() {
@@ -694,6 +737,34 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
             ++c_ph;
             c_c = 0;
         }
+    };
+    // this wave's share of chunk c_c of the current phase (registers only: may run ahead of the phase's wait)
+    auto chunk_setup = [&](const auto &P) {
+        const int scc = min(P.SC, P.S - c_c * P.SC);
+        const int s_lo = (scc * w) / NW;
+        const int spw = (scc * (w + 1)) / NW - s_lo;
+        c_nsl = max(spw, 1);
+        if constexpr (ROLES == 2) {
+            // the first of the two 16th-parts of the chunk that this wave covers
+            c_h0 = (scc * (2 * w + 1)) / (2 * NW) - s_lo;
+            c_half = c_h0 > 0 ? c_h0 : kForever;
+        }
+        if constexpr (A8) {
+            c_xinc = spw > 0 ? (unsigned int)(PPS * MP * 16) : 0u;
+            c_x0 = spw > 0 ? (unsigned int)s_lo * (unsigned int)(PPS * MP * 16) : 0u;
+        } else {
+            const unsigned int rs = (unsigned int)(P.SC * KSTEP * 2 + 16);
+            xlane = (unsigned int)xm * rs + (unsigned int)((W16 ? g : 2 * g) * 16);
+            xrow16 = 16u * rs;
+            c_xinc = spw > 0 ? (unsigned int)(KSTEP * 2) : 0u;
+            c_x0 = spw > 0 ? (unsigned int)s_lo * (unsigned int)(KSTEP * 2) : 0u;
+        }
+        c_tl = 0;
+        c_left = c_nsl;
+        c_xoff = c_x0;
+        unit_left = (c_ntiles * c_nsl + GR - 1) & ~(GR - 1);
+        nocomp = false;
+        c_reseg();
     };
     // enter the next (phase, chunk): take part in the phase's wait, stage scales and
     // activations.  Returns false when the sequence is finished.
@@ -718,13 +789,46 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
                 // other waves still read of the old layout is read before they pass the barrier below)
                 lay_out(P.xs_bytes, P.sc_bytes);
                 stamp(c_ph, 0);
+            }
+            // Everything that needs no memory of the producers is worked out in front of the phase's wait: this
+            // wave's share of the chunk and the addresses of its activation loads.  (On the hand-over path the
+            // sixteen waves of a workgroup run this scalar code side by side, four to a SIMD; done after the wait,
+            // the youngest wave of a SIMD reached its first load 1.5 us after the flags had been seen.)
+            chunk_setup(P);
+            const bool direct = !A8 && P.wait != SEQ_WAIT_BARRIER;
+            XPlan xpl{};
+            if (direct)
+                xpl = x_plan(P, (long long)c_c * P.SC * KSTEP, min(P.SC, P.S - c_c * P.SC) * KSTEP,
+                             (unsigned int)(P.SC * KSTEP * 2 + 16));
+            // (uses that cannot move: without them the compiler sinks these computations, phase-table reads
+            // included, behind the wait and into the first tile's epilogue)
+            asm volatile("" ::"v"(c_x0), "v"(c_xinc), "v"(c_nsl), "v"(unit_left), "v"(xlane), "v"(c_seg_end), "v"(c_tb),
+                         "v"((unsigned int)c_ldy), "v"((unsigned int)(unsigned long long)c_y));
+            asm volatile("" ::"v"((unsigned int)xpl.x0), "v"((unsigned int)xpl.ld2), "v"(xpl.m), "v"(xpl.i), "v"(xpl.dq), "v"(xpl.dr),
+                         "v"(xpl.count), "v"(xpl.rowbytes), "v"(xpl.rs));
+            if (c_c == 0) {
+                // The row scales do not depend on anybody either.  While wave 0 polls the producers' flags the other
+                // waves request them, and store them once the previous phase's last epilogue has read its own.
+                // (Wave 0 takes no part: a load pending across its poll loop would make the compiler stop counting
+                // the ring's loads.)
+                sc_early = !W16 && !A8 && P.wait == SEQ_WAIT_FLAGS && c_ntiles > 0 &&
+                           c_ntiles * (kTileRows / 2) <= nthreads - 64;
+                unsigned int sc_pre = 0u;
                 if (P.wait != SEQ_WAIT_BARRIER) {
                     if (P.wait == SEQ_WAIT_FLAGS) {
-                        flags_wait(P.producer[0]);
-                        if (P.producer[1] >= 0) flags_wait(P.producer[1]);
+                        if (w == 0) {
+                            flags_wait(P.producer[0]);
+                            if (P.producer[1] >= 0) flags_wait(P.producer[1]);
+                        } else if (sc_early) {
+                            sc_pre = scale_fetch(P, c_t0, c_ntiles, tid - 64);
+                        }
                     }
                     lds_barrier();   // flags seen by all; the previous phase's last epilogue has read its scales
                 }
+                // (an explicit wait on every path: the compiler then knows the load queue empty here, whatever path
+                // follows; the scales have had the whole flag wait to arrive)
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                if (sc_early) scale_put(c_ntiles, tid - 64, sc_pre);
                 stamp(c_ph, 1);
                 if (c_ntiles == 0) {   // nothing to do here but the waits
                     c_c = c_C - 1;
@@ -734,7 +838,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
                 if constexpr (A8) {
                     if (P.raw_off != 0) {
                         // scales and activations are requested together; everything is waited for once
-                        x_direct(P, 0, (P.K / 8) * MP, (unsigned int)P.raw_off);
+                        x_direct(P, 0, P.K, (unsigned int)P.raw_off, (unsigned int)(P.K * 2 + 16));
                         scale_stage_one_trip(P, c_t0, c_ntiles);
                         __builtin_amdgcn_s_waitcnt(0x0F70);
                         x_scan_quant_lds(P);
@@ -744,31 +848,15 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
                     }
                 }
             }
-            const int scc = min(P.SC, P.S - c_c * P.SC);
-            const int s_lo = (scc * w) / NW;
-            const int spw = (scc * (w + 1)) / NW - s_lo;
-            c_nsl = max(spw, 1);
-            if constexpr (ROLES == 2) {
-                // the first of the two 16th-parts of the chunk that this wave covers
-                c_h0 = (scc * (2 * w + 1)) / (2 * NW) - s_lo;
-                c_half = c_h0 > 0 ? c_h0 : kForever;
-            }
-            c_xinc = spw > 0 ? (unsigned int)(PPS * MP * 16) : 0u;
-            c_x0 = spw > 0 ? (unsigned int)s_lo * (unsigned int)(PPS * MP * 16) : 0u;
-            c_tl = 0;
-            c_left = c_nsl;
-            c_xoff = c_x0;
-            unit_left = (c_ntiles * c_nsl + GR - 1) & ~(GR - 1);
-            nocomp = false;
-            c_reseg();
             if constexpr (A8) {
                 if (P.raw_off == 0) x_quant(P, c_c, P.wait == SEQ_WAIT_BARRIER);
             } else {
-                // activations and row scales are requested together and waited for once: one round trip,
-                // not two (the activations first: they go straight to LDS, so no loaded value is held across
-                // their issue loop)
-                x_stage(P, c_c, P.wait == SEQ_WAIT_BARRIER);
-                if (c_c == 0) scale_stage_one_trip(P, c_t0, c_ntiles);
+                // activations and (where they were not requested ahead) row scales are requested together and waited
+                // for once: one round trip, not two (the activations first: they go straight to LDS, so no loaded
+                // value is held across their issue loop)
+                if (direct) x_issue(xpl, 0u);
+                else x_stage(P, c_c, true);
+                if (c_c == 0 && !sc_early) scale_stage_one_trip(P, c_t0, c_ntiles);
             }
             // known-empty load queue: keeps the counted waits of the ring exact (see stream_gemm.hpp)
             __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -819,14 +907,14 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
                 c_xoff += c_xinc;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const u32x4 b0 = *reinterpret_cast<const u32x4 *>(xp + nb * 256);
+                    const u32x4 b0 = *reinterpret_cast<const u32x4 *>(xp + (A8 ? nb * 256 : nb * xrow16));
                     if constexpr (A8) {
                         acci[nb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, wv),
                                                                          __builtin_bit_cast(i32x4, b0), acci[nb], 0, 0, 0);
                     } else {
                         acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0), acc[nb], 0, 0, 0);
                         if constexpr (!W16) {
-                            const u32x4 b1 = *reinterpret_cast<const u32x4 *>(xp + nb * 256 + MP * 16);
+                            const u32x4 b1 = *reinterpret_cast<const u32x4 *>(xp + nb * xrow16 + 16);
                             acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1), acc[nb], 0, 0, 0);
                         }
                     }
