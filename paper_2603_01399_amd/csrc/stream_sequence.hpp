@@ -385,8 +385,9 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     // in different banks).  One instruction moves 1 KB that is contiguous in memory AND in LDS - measured on all
     // 256 compute units fetching the same 64 KB: 100 GB/s per compute unit, against 35 GB/s when an instruction
     // gathers 128 bytes from each of eight rows (rows are a multiple of 4 KB apart and meet in one cache channel).
-    // Rows past M repeat row M - 1: their results are never used.  Instruction j covers piece j % ipr of token
-    // j / ipr; wave w takes j = w, w + NW, ...
+    // Rows past M repeat row M - 1: their results are never used.  Instruction j covers 1 KB piece j / MP of token
+    // j % MP (the waves that issue together then read from different rows: measured 0.93 us for 64 KB against
+    // 1.03 us with a row after the other, and the index arithmetic needs no division); wave w takes j = w, w + NW, ...
     // The work is split in two: x_plan does the arithmetic (divisions included) and may run while the wave would
     // otherwise idle in front of the phase's wait; x_issue then costs a dozen scalar instructions per load.  (On
     // the hand-over path the sixteen waves of a workgroup execute this code side by side, four to a SIMD, and the
@@ -394,17 +395,12 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     struct XPlan {
         unsigned long long x0, ld2;
         unsigned int rs;
-        int m, i, dq, dr, ipr, count, rowbytes;
+        int count, rowbytes;
     };
     auto x_plan = [&](const auto &P, long long k0, int ncols, unsigned int rs) -> XPlan {
         XPlan pl;
         pl.rowbytes = ncols * 2;
-        pl.ipr = (pl.rowbytes + 1023) >> 10;
-        const int ninstr = pl.ipr * MP;
-        pl.m = w / pl.ipr;
-        pl.i = w - pl.m * pl.ipr;
-        pl.dq = NW / pl.ipr;
-        pl.dr = NW - pl.dq * pl.ipr;
+        const int ninstr = ((pl.rowbytes + 1023) >> 10) * MP;
         pl.count = w < ninstr ? (ninstr - w + NW - 1) / NW : 0;
         pl.x0 = reinterpret_cast<unsigned long long>(P.x) + 2ull * (unsigned long long)k0;
         pl.ld2 = (unsigned long long)P.ldx * 2ull;
@@ -413,8 +409,9 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     };
     auto x_issue = [&](const XPlan &pl, unsigned int dst) {
         const unsigned int x_voff = (unsigned int)lane * 16u;
-        int m = pl.m, i = pl.i;
         for (int n = 0; n < pl.count; ++n) {
+            const int j = w + n * NW;
+            const int m = j & (MP - 1), i = j >> LMP;
             const unsigned long long gb = pl.x0 + (unsigned long long)min(m, M - 1) * pl.ld2 + (unsigned long long)i * 1024ull;
             const unsigned int glo = __builtin_amdgcn_readfirstlane((unsigned int)gb);
             const unsigned int ghi = __builtin_amdgcn_readfirstlane((unsigned int)(gb >> 32));
@@ -422,9 +419,6 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
             const unsigned int laddr = __builtin_amdgcn_readfirstlane(lds_base + dst + (unsigned int)m * pl.rs + (unsigned int)i * 1024u);
             if (i * 1024 + 1024 <= pl.rowbytes) load_to_lds_16(gbase, x_voff, laddr);
             else if (i * 1024 + lane * 16 < pl.rowbytes) load_to_lds_16(gbase, x_voff, laddr);
-            i += pl.dr;
-            m += pl.dq;
-            if (i >= pl.ipr) { i -= pl.ipr; ++m; }
         }
     };
     auto x_direct = [&](const auto &P, long long k0, int ncols, unsigned int dst, unsigned int rs) {
@@ -463,7 +457,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     // hits the caches.
     const int m_own = tid & (MP - 1);
     float a8_inv = 0.f;
-    constexpr int AXB = 3;       // pieces per thread and batch (four would spill)
+    constexpr int AXB = MP == 8 ? 3 : 2;   // pieces per thread and batch (more would spill)
     auto a8_load = [&](const auto &P, long long k, bool coherent) -> u32x4 {
         if (coherent) return coherent_load_u32x4(P.x + m_own * P.ldx + k);
         return *as_global(reinterpret_cast<const u32x4 *>(P.x + m_own * P.ldx + k));
@@ -794,7 +788,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
             // wave's share of the chunk and the addresses of its activation loads.  (On the hand-over path the
             // sixteen waves of a workgroup run this scalar code side by side, four to a SIMD; done after the wait,
             // the youngest wave of a SIMD reached its first load 1.5 us after the flags had been seen.)
-            chunk_setup(P);
+            if constexpr (!A8) chunk_setup(P);
             const bool direct = !A8 && P.wait != SEQ_WAIT_BARRIER;
             XPlan xpl{};
             if (direct)
@@ -802,10 +796,15 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
                              (unsigned int)(P.SC * KSTEP * 2 + 16));
             // (uses that cannot move: without them the compiler sinks these computations, phase-table reads
             // included, behind the wait and into the first tile's epilogue)
-            asm volatile("" ::"v"(c_x0), "v"(c_xinc), "v"(c_nsl), "v"(unit_left), "v"(xlane), "v"(c_seg_end), "v"(c_tb),
-                         "v"((unsigned int)c_ldy), "v"((unsigned int)(unsigned long long)c_y));
-            asm volatile("" ::"v"((unsigned int)xpl.x0), "v"((unsigned int)xpl.ld2), "v"(xpl.m), "v"(xpl.i), "v"(xpl.dq), "v"(xpl.dr),
-                         "v"(xpl.count), "v"(xpl.rowbytes), "v"(xpl.rs));
+            if constexpr (!A8) {
+                auto pin = [](unsigned int v) { asm volatile("" ::"s"(v)); };
+                pin(c_x0); pin(c_xinc); pin((unsigned int)c_nsl); pin((unsigned int)unit_left);
+                pin((unsigned int)c_seg_end); pin((unsigned int)c_tb); pin((unsigned int)c_ldy);
+                pin((unsigned int)(unsigned long long)c_y);
+                pin((unsigned int)xpl.x0); pin((unsigned int)xpl.ld2); pin((unsigned int)xpl.count);
+                pin((unsigned int)xpl.rowbytes); pin(xpl.rs);
+                asm volatile("" ::"v"(xlane));
+            }
             if (c_c == 0) {
                 // The row scales do not depend on anybody either.  While wave 0 polls the producers' flags the other
                 // waves request them, and store them once the previous phase's last epilogue has read its own.
@@ -849,6 +848,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
                 }
             }
             if constexpr (A8) {
+                chunk_setup(P);   // (behind the scan: its registers are not held across it)
                 if (P.raw_off == 0) x_quant(P, c_c, P.wait == SEQ_WAIT_BARRIER);
             } else {
                 // activations and (where they were not requested ahead) row scales are requested together and waited
