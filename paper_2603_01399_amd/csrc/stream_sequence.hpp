@@ -579,11 +579,23 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
         for (int t0 = 4 * lane; t0 < GW; t0 += 256) {
             for (;;) {
                 unsigned int f[4];
+                // One 128-bit device-coherent load per lane and poll (the flags are independent words: tearing between
+                // them does not matter): a quarter of the requests of four 32-bit loads, measured 0.2 us less from
+                // "flag up" to "flag seen".  Load and wait form one statement, so the compiler's count of the ring's
+                // outstanding loads is not involved (everything older has landed once this returns).
+                if (t0 + 3 < GW) {
+                    u32x4 v;
+                    asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)"
+                                 : "=&v"(v)
+                                 : "v"(as_global(row + t0))
+                                 : "memory");
+                    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+                } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    f[i] = t0 + i < GW ? __hip_atomic_load(as_global(row + t0 + i), __ATOMIC_RELAXED,
-                                                          __HIP_MEMORY_SCOPE_AGENT)
-                                      : epoch;
+                    for (int i = 0; i < 4; ++i)
+                        f[i] = t0 + i < GW ? __hip_atomic_load(as_global(row + t0 + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                          : epoch;
+                }
                 if (f[0] == epoch && f[1] == epoch && f[2] == epoch && f[3] == epoch) break;
                 // (the error word is only read on this path: a load still pending when the loop is left would
                 // make the compiler give up counting the ring's outstanding loads and drain it at every slot)
