@@ -196,7 +196,6 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
     const int nph = sp.nphases;
     const const_phase_ptr phases = (const_phase_ptr)(unsigned long long)sp.phases;
 
-    u32x4 *xs = reinterpret_cast<u32x4 *>(lds);
     // regions behind the activations; moved at every phase entry to that phase's own sizes
     uint16_t *sc_lds = reinterpret_cast<uint16_t *>(lds + sp.xs_bytes);
     // the last 256 bytes of the scale region: per-token step sizes and maxima of the W8A8 form
