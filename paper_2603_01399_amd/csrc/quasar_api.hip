@@ -105,7 +105,8 @@ Plan make_plan(int T, int S, int x_bytes_per_step, int unit_bytes, int NW, bool 
     Plan pl{};
     pl.S = S;
     choose_chunks(S, x_bytes_per_step, 2 * NW * unit_bytes, pl.SC, pl.C);
-    pl.xs_bytes = pl.SC * x_bytes_per_step;
+    // (+ 512: activations kept as token rows lie 16 bytes further apart than their length, at most 32 rows)
+    pl.xs_bytes = pl.SC * x_bytes_per_step + 512;
     const int stage = 2 * NW * unit_bytes;
     int grid = grid_want > 0 ? grid_want : device_cus() * g_tune_wgs.load();
     if (grid > T) grid = T;

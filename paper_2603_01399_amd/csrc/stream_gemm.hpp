@@ -193,6 +193,14 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
     // operand per piece: half the batch keeps the register count of the plain kernel)
     constexpr int XB = PRE == PRE_NONE ? 8 : 4;
     constexpr int nthreads = NW * 64;
+    // Without a fused staging operation the activations go straight from memory into LDS, as token rows: token m
+    // at m * rs (rs = a chunk's row bytes + 16: the skew keeps the tokens of one column in different banks).  One
+    // load instruction moves 1 KB that is contiguous in memory and in LDS and holds no registers; instruction j is
+    // 1 KB piece j / MP of token j % MP, wave w takes j = w, w + NW, ...  (With all compute units fetching the
+    // same 64 KB this pattern is 2-3x faster than gathering 128 bytes from each of eight rows per instruction:
+    // rows are a multiple of 4 KB apart and meet in one cache channel.)  The fused forms (normalisation while
+    // staging) keep the path through registers and the [k/8][token][8] layout.
+    constexpr bool ROWS = PRE == PRE_NONE;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -242,7 +250,29 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
         if constexpr (PRE == PRE_RMSNORM) return pre_rmsnorm_piece(x, aux, r_own);
         else return x;
     };
+    [[maybe_unused]] const unsigned int x_rs = (unsigned int)(p.SC * KSTEP * 2 + 16);
+    [[maybe_unused]] auto x_rows = [&](int c) {
+        const unsigned int lds_base = lds_address_of(lds);
+        const int rowbytes = min(p.SC, p.S - c * p.SC) * KSTEP * 2;
+        const int ninstr = ((rowbytes + 1023) >> 10) * MP;
+        const unsigned long long x0 = reinterpret_cast<unsigned long long>(p.x) + 2ull * (unsigned long long)c * p.SC * KSTEP;
+        const unsigned long long ld2 = (unsigned long long)p.ldx * 2ull;
+        for (int j = w; j < ninstr; j += NW) {
+            const int m = j & (MP - 1), i = j >> LMP;
+            const unsigned long long gb = x0 + (unsigned long long)min(m, p.M - 1) * ld2 + (unsigned long long)i * 1024ull;
+            const unsigned int glo = __builtin_amdgcn_readfirstlane((unsigned int)gb);
+            const unsigned int ghi = __builtin_amdgcn_readfirstlane((unsigned int)(gb >> 32));
+            const unsigned long long gbase = ((unsigned long long)ghi << 32) | glo;
+            const unsigned int laddr = __builtin_amdgcn_readfirstlane(lds_base + (unsigned int)m * x_rs + (unsigned int)i * 1024u);
+            if (i * 1024 + 1024 <= rowbytes) load_to_lds_16(gbase, (unsigned int)lane * 16u, laddr);
+            else if (i * 1024 + lane * 16 < rowbytes) load_to_lds_16(gbase, (unsigned int)lane * 16u, laddr);
+        }
+    };
     auto x_stage = [&](int c, int first_batch) {
+        if constexpr (ROWS) {
+            x_rows(c);
+            return;
+        }
         const int scc = min(p.SC, p.S - c * p.SC);
         const int npieces = scc * PPS * MP;
         for (int base = first_batch * nthreads * XB; base < npieces; base += nthreads * XB) {
@@ -268,10 +298,14 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
     typename WaveWalk<NW, D>::Front ld;
     walk.begin(ld);
 
-    // requests in the order they are needed back: first activation batch, scales, weight ring
-    u32x4 xfirst[XB];
+    // requests in the order they are needed back: activations (first batch), scales, weight ring
+    u32x4 xfirst[ROWS ? 1 : XB];
+    if constexpr (ROWS) {
+        x_rows(0);
+    } else {
 #pragma unroll
-    for (int i = 0; i < XB; ++i) xfirst[i] = x_piece_load(0, i * nthreads + tid);
+        for (int i = 0; i < XB; ++i) xfirst[i] = x_piece_load(0, i * nthreads + tid);
+    }
     u32x4 afirst[PRE != PRE_NONE ? XB : 1];
     if constexpr (PRE != PRE_NONE) {
 #pragma unroll
@@ -331,13 +365,15 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
         __builtin_amdgcn_s_waitcnt(0x0F70);
     }
     {
-        const int npieces = min(p.SC, p.S) * PPS * MP;
+        if constexpr (!ROWS) {
+            const int npieces = min(p.SC, p.S) * PPS * MP;
 #pragma unroll
-        for (int i = 0; i < XB; ++i) {
-            const int idx = i * nthreads + tid;
-            if (idx < npieces) {
-                if constexpr (PRE != PRE_NONE) xs[idx] = pre_apply(xfirst[i], afirst[i]);
-                else xs[idx] = xfirst[i];
+            for (int i = 0; i < XB; ++i) {
+                const int idx = i * nthreads + tid;
+                if (idx < npieces) {
+                    if constexpr (PRE != PRE_NONE) xs[idx] = pre_apply(xfirst[i], afirst[i]);
+                    else xs[idx] = xfirst[i];
+                }
             }
         }
         if constexpr (!W16) {
@@ -346,7 +382,13 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                 reinterpret_cast<unsigned int *>(sc_lds)[i >> 1] =
                     *reinterpret_cast<const unsigned int *>(p.scales + (long long)t0 * kTileRows + i);
         }
-        x_stage(0, 1);
+        if constexpr (ROWS) {
+            // the direct-to-LDS loads were issued first and loads return in order: once no more than the D ring
+            // loads are outstanding, this wave's share of the activations is in LDS
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(D) : "memory");
+        } else {
+            x_stage(0, 1);
+        }
         lds_barrier();
     }
 
@@ -359,6 +401,8 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
     for (int nb = 0; nb < NB; ++nb) { bestv[nb] = -__builtin_inff(); besti[nb] = 0x7FFFFFFFu; }
     int parity = 0;
     const int xm = (MP == 8) ? (mcol & 7) : mcol;   // token slot read by this lane
+    // token rows: this lane's B operand of step s, piece q is at xm * rs + (s * PPS + q) * 16
+    [[maybe_unused]] const unsigned char *xrow = lds + (unsigned int)xm * x_rs;
 
     for (int c = 0; c < p.C; ++c) {
         if (c > 0) {
@@ -391,8 +435,15 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                     walk.advance(ld);
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
-                        const u32x4 b0 = xs[(piece0 + 2 * g) * MP + xm + 16 * nb];
-                        const u32x4 b1 = xs[(piece0 + 2 * g + 1) * MP + xm + 16 * nb];
+                        u32x4 b0, b1;
+                        if constexpr (ROWS) {
+                            const unsigned char *q = xrow + (unsigned int)(16 * nb) * x_rs + (unsigned int)(piece0 + 2 * g) * 16u;
+                            b0 = *reinterpret_cast<const u32x4 *>(q);
+                            b1 = *reinterpret_cast<const u32x4 *>(q + 16);
+                        } else {
+                            b0 = xs[(piece0 + 2 * g) * MP + xm + 16 * nb];
+                            b1 = xs[(piece0 + 2 * g + 1) * MP + xm + 16 * nb];
+                        }
                         acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0),
                                                                           acc[nb], 0, 0, 0);
                         acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, b1),
@@ -402,7 +453,12 @@ __global__ __launch_bounds__(NW * 64) void stream_mfma_kernel(const GemmParams p
                     const bf16x8 a0 = __builtin_bit_cast(bf16x8, wv);
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
-                        const u32x4 b0 = xs[(piece0 + g) * MP + xm + 16 * nb];
+                        u32x4 b0;
+                        if constexpr (ROWS)
+                            b0 = *reinterpret_cast<const u32x4 *>(xrow + (unsigned int)(16 * nb) * x_rs +
+                                                                  (unsigned int)(piece0 + g) * 16u);
+                        else
+                            b0 = xs[(piece0 + g) * MP + xm + 16 * nb];
                         acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, __builtin_bit_cast(bf16x8, b0),
                                                                           acc[nb], 0, 0, 0);
                     }

@@ -109,22 +109,6 @@ __device__ __forceinline__ u32x4 coherent_load_u32x4(const void *p) {
     const unsigned long long hi = coherent_load_u64(static_cast<const unsigned long long *>(p) + 1);
     return u32x4{(unsigned int)lo, (unsigned int)(lo >> 32), (unsigned int)hi, (unsigned int)(hi >> 32)};
 }
-// 16 bytes per lane from gbase + lane_offset (gbase wave-uniform) straight into LDS at lds_addr + 16 * lane,
-// without passing through registers.  Inline assembly on purpose: when the compiler sees a direct-to-LDS
-// load anywhere in a kernel it makes every LDS read wait for ALL outstanding vector memory loads (it
-// cannot tell which loads write LDS), which would drain the weight ring at every slot.  The caller waits
-// for these loads explicitly (vmcnt(0)) before anybody reads the bytes.
-__device__ __forceinline__ void load_to_lds_16(unsigned long long gbase, unsigned int lane_offset, unsigned int lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(lane_offset), "s"(gbase), "s"(lds_addr)
-                 : "memory");   // (M0 is reserved: the compiler keeps nothing in it across statements)
-}
-__device__ __forceinline__ unsigned int lds_address_of(const unsigned char *p) {
-    return __builtin_amdgcn_readfirstlane(
-        (unsigned int)(unsigned long long)((const __attribute__((address_space(3))) unsigned char *)p));
-}
-
 // All workgroups of the launch meet.  Every wave first waits until its own (coherent) stores
 // have been acknowledged, so whatever the workgroup wrote is readable device-wide once the
 // arrival counter has been bumped.  Polling is bounded in TIME (spin_limit ticks of the 100 MHz
