@@ -636,23 +636,24 @@ bool plan_w4(int T, int S, int MP, int NW, PlanW4 &pl) {
     const int xps = 272 * MP;
     int grid = device_cus();
     if (grid > T) grid = T;
-    if ((long long)S * xps + stage + 64 <= kMaxLds) {
+    // (+ 512: the activations lie in LDS as token rows 16 bytes further apart than their length, at most 32 rows)
+    if ((long long)S * xps + 512 + stage + 64 <= kMaxLds) {
         pl.SC = S;
         pl.C = 1;
-        pl.xs_bytes = S * xps;
+        pl.xs_bytes = S * xps + 512;
         pl.lds_bytes = pl.xs_bytes + stage;
     } else {
         const int want = S < 8 ? S : 8;      // steps per chunk worth having
         for (;;) {
             const int tpw = (T + grid - 1) / grid;
             const int sums = ((tpw + 1) / 2) * 2 * NB * 1024;
-            const int per = (kMaxLds - stage - sums - 64) / xps;
+            const int per = (kMaxLds - stage - sums - 64 - 512) / xps;
             const bool can_grow = grid < T && grid * 2 <= kMaxGrid;
             if (per >= want || (per >= 1 && !can_grow)) {
                 pl.C = (S + per - 1) / per;
                 pl.SC = (S + pl.C - 1) / pl.C;
                 pl.C = (S + pl.SC - 1) / pl.SC;
-                pl.xs_bytes = pl.SC * xps;
+                pl.xs_bytes = pl.SC * xps + 512;
                 pl.lds_bytes = pl.xs_bytes + stage + sums;
                 break;
             }

@@ -61,7 +61,8 @@ __device__ __forceinline__ u32x2 ring_refill2_at(unsigned long long base, unsign
     return __builtin_nontemporal_load(reinterpret_cast<global_u32x2_ptr>(base + lane_offset));
 }
 
-// LDS: [activation chunk: [k/8][token] 16 B][group offsets: [step][token] f32x4]
+// LDS: [activation chunk: token rows, token m at m * (row bytes + 16), fetched straight from memory][group
+//      offsets: [step][token] f32x4]
 //      [PAR x NW x 2 staging tiles][pair sums (C > 1)]
 // p.xs_bytes covers the first two; p.sc_bytes is 0.  PAR = 2 staging areas used alternately
 // (one barrier per pair) when they fit, else one area and a second barrier.
@@ -72,7 +73,6 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
     constexpr int PAR = (NB == 1) ? 2 : 1;
     constexpr int PPS = 16;                  // 16-byte activation pieces (8 k) per step
     constexpr int LMP = (MP == 8) ? 3 : (MP == 16 ? 4 : 5);
-    constexpr int XB = 8;
     constexpr int nthreads = NW * 64;
 
     const int tid = threadIdx.x;
@@ -86,36 +86,32 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
     const int ntiles = t1 - t0;
     const int npairs = (ntiles + 1) >> 1;
 
-    u32x4 *xs = reinterpret_cast<u32x4 *>(lds);                                   // [SC*PPS][MP]
-    f32x4 *gofs = reinterpret_cast<f32x4 *>(lds + p.SC * PPS * MP * 16);          // [SC][MP]
+    // activations: 16-byte piece p8 (8 k) of token m at m * x_rs + 16 * p8 (the 16-byte skew keeps the tokens of
+    // one column in different banks); one direct-to-LDS load instruction moves 1 KB that is contiguous in memory
+    // and in LDS - instruction j is 1 KB piece j / MP of token j % MP, wave w takes j = w, w + NW, ...
+    const unsigned int x_rs = (unsigned int)(p.SC * kStepK4 * 2 + 16);
+    auto xq = [&](int p8, int m) -> u32x4 {
+        return *reinterpret_cast<const u32x4 *>(lds + (unsigned int)m * x_rs + (unsigned int)p8 * 16u);
+    };
+    f32x4 *gofs = reinterpret_cast<f32x4 *>(lds + MP * x_rs);                      // [SC][MP]
     f32x4 *stage = reinterpret_cast<f32x4 *>(lds + p.xs_bytes);                   // [PAR][NW][2][NB][64]
     f32x4 *accs = stage + PAR * NW * 2 * NB * 64;                                 // [npairs][2][NB][64] (C > 1)
 
-    auto x_piece_load = [&](int c, int idx) -> u32x4 {
-        const int scc = min(p.SC, p.S - c * p.SC);
-        const int npieces = scc * PPS * MP;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (idx < npieces) {
-            const int m = idx & (MP - 1), p8 = idx >> LMP;
-            if (m < p.M) {
-                const long long k = (long long)c * p.SC * kStepK4 + 8ll * p8;
-                v = *reinterpret_cast<const u32x4 *>(p.x + m * p.ldx + k);
-            }
-        }
-        return v;
-    };
-    auto x_stage = [&](int c, int first_batch) {
-        const int scc = min(p.SC, p.S - c * p.SC);
-        const int npieces = scc * PPS * MP;
-        for (int base = first_batch * nthreads * XB; base < npieces; base += nthreads * XB) {
-            u32x4 v[XB];
-#pragma unroll
-            for (int i = 0; i < XB; ++i) v[i] = x_piece_load(c, base + i * nthreads + tid);
-#pragma unroll
-            for (int i = 0; i < XB; ++i) {
-                const int idx = base + i * nthreads + tid;
-                if (idx < npieces) xs[idx] = v[i];
-            }
+    auto x_stage = [&](int c) {
+        const unsigned int lds_base = lds_address_of(lds);
+        const int rowbytes = min(p.SC, p.S - c * p.SC) * kStepK4 * 2;
+        const int ninstr = ((rowbytes + 1023) >> 10) * MP;
+        const unsigned long long x0 = reinterpret_cast<unsigned long long>(p.x) + 2ull * (unsigned long long)c * p.SC * kStepK4;
+        const unsigned long long ld2 = (unsigned long long)p.ldx * 2ull;
+        for (int j = w; j < ninstr; j += NW) {
+            const int m = j & (MP - 1), i = j >> LMP;
+            const unsigned long long gb = x0 + (unsigned long long)min(m, p.M - 1) * ld2 + (unsigned long long)i * 1024ull;
+            const unsigned int glo = __builtin_amdgcn_readfirstlane((unsigned int)gb);
+            const unsigned int ghi = __builtin_amdgcn_readfirstlane((unsigned int)(gb >> 32));
+            const unsigned long long gbase = ((unsigned long long)ghi << 32) | glo;
+            const unsigned int laddr = __builtin_amdgcn_readfirstlane(lds_base + (unsigned int)m * x_rs + (unsigned int)i * 1024u);
+            if (i * 1024 + 1024 <= rowbytes) load_to_lds_16(gbase, (unsigned int)lane * 16u, laddr);
+            else if (i * 1024 + lane * 16 < rowbytes) load_to_lds_16(gbase, (unsigned int)lane * 16u, laddr);
         }
     };
     // -136 * (sum of a group's activations) per (step of the chunk, token), four copies so that
@@ -132,7 +128,7 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
             if (idx < scc * MP) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const u32x4 v = xs[(s * PPS + 4 * q + j) * MP + m];
+                    const u32x4 v = xq(s * PPS + 4 * q + j, m);
                     sum += __uint_as_float(v.x << 16);
                     sum += __uint_as_float(v.x & 0xFFFF0000u);
                     sum += __uint_as_float(v.y << 16);
@@ -200,10 +196,8 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
     ld.c = 0;
     lf_slice(ld);
 
-    // requests in the order they are needed back: first activation batch, then the ring
-    u32x4 xfirst[XB];
-#pragma unroll
-    for (int i = 0; i < XB; ++i) xfirst[i] = x_piece_load(0, i * nthreads + tid);
+    // requests in the order they are needed back: the activations (straight into LDS), then the ring
+    x_stage(0);
     u32x4 ringA[D], ringB[D];
     u32x2 sclA[D], sclB[D];
 #pragma unroll
@@ -219,13 +213,9 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
         lf_advance(ld);
     }
     {
-        const int npieces = min(p.SC, p.S) * PPS * MP;
-#pragma unroll
-        for (int i = 0; i < XB; ++i) {
-            const int idx = i * nthreads + tid;
-            if (idx < npieces) xs[idx] = xfirst[i];
-        }
-        x_stage(0, 1);
+        // loads return in order: once no more than the 4 D ring loads are outstanding, this wave's share of the
+        // activations is in LDS
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * D) : "memory");
         lds_barrier();
         group_offsets(0);
         lds_barrier();
@@ -247,7 +237,7 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
         if (c > 0) {
             // every wave has passed the previous chunk's last pair barrier: the chunk's
             // activations are no longer read
-            x_stage(c, 0);
+            x_stage(c);
             // full drain: the staging loads are conditional, and without a known-empty load
             // queue here the compiler would fall back to draining the ring on every round
             __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -289,7 +279,7 @@ __global__ __launch_bounds__(NW * 64) void stream_w4_kernel(const GemmParams p) 
                         const bf16x8 aB = w4_to_bf16x8(wdB[j], nib_mask, nib_magic);
 #pragma unroll
                         for (int nb = 0; nb < NB; ++nb) {
-                            const bf16x8 bx = __builtin_bit_cast(bf16x8, xs[(piece0 + 4 * j + g) * MP + xm + 16 * nb]);
+                            const bf16x8 bx = __builtin_bit_cast(bf16x8, xq(piece0 + 4 * j + g, xm + 16 * nb));
                             gA[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aA, bx, gA[nb], 0, 0, 0);
                             gB[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aB, bx, gB[nb], 0, 0, 0);
                         }
