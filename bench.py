@@ -285,7 +285,8 @@ def main() -> int:
             assert torch.equal(kept[li][k].view(torch.int16), bufs[li][k].view(torch.int16)), \
                 f"timed launch differs from the single calls at layer {li} output {k}"
     assert torch.equal(kept_am, out_argmax) and torch.equal(kept_acc, out_accept), \
-        "timed launch's argmax / accepted length differ from the single call's"
+        ("timed launch's argmax / accepted length differ from the single call's: "
+         f"{kept_am.tolist()} / {kept_acc.tolist()} against {out_argmax.tolist()} / {out_accept.tolist()}")
     log(f"timed launch verified against the single calls: {7 * L} outputs, argmax and accepted length "
         f"({int(kept_acc[0])}) bit-identical")
     del kept

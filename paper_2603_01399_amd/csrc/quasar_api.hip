@@ -738,20 +738,24 @@ int sequence_residency_of(int MP, bool w16, bool a8, int lds_bytes) {
 extern "C" {
 
 constexpr size_t kSeqZeroBytes = 1024;
+// A vocabulary phase whose per-tile running sums do not fit the LDS is split into several phases over tile ranges:
+// room for that many more table entries and flag rows than there are linears
+constexpr int kSeqExtraPhases = 16;
+constexpr size_t seq_table_phases(int64_t n_linears) { return (size_t)(n_linears + 1 + kSeqExtraPhases); }
 
 size_t quasar_sequence_plan_bytes(int64_t n_linears) {
     if (n_linears < 0 || n_linears > (1 << 20)) return 0;
-    return (size_t)(n_linears + 1) * sizeof(SeqPhase) + kSeqZeroBytes;   // phase table, block of zeros
+    return seq_table_phases(n_linears) * sizeof(SeqPhase) + kSeqZeroBytes;   // phase table, block of zeros
 }
 
-// workspace: [sync words, then one counter per compute-unit id][argmax partials][completion flags: (n_linears + 1) x grid]
+// workspace: [sync words, then one counter per compute-unit id][argmax partials][completion flags: (n_linears + 1 + spare) x grid]
 constexpr size_t kSeqHeaderBytes = 16 * 1024;
 static_assert((64 + kSeqCuSlots) * sizeof(unsigned int) <= kSeqHeaderBytes, "header holds the counters");
 constexpr size_t kSeqPartialBytes = (size_t)kMaxGrid * 32u * sizeof(unsigned long long);
 
 size_t quasar_sequence_workspace_bytes(int64_t n_linears, int64_t M) {
     if (M < 1 || M > 32 || n_linears < 0 || n_linears > (1 << 20)) return 0;
-    return kSeqHeaderBytes + kSeqPartialBytes + (size_t)(n_linears + 1) * kMaxGrid * sizeof(unsigned int);
+    return kSeqHeaderBytes + kSeqPartialBytes + seq_table_phases(n_linears) * kMaxGrid * sizeof(unsigned int);
 }
 
 static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_linears, const float *const *smooth,
@@ -901,7 +905,34 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
         const Range xr{reinterpret_cast<uintptr_t>(v.hidden), reinterpret_cast<uintptr_t>(v.hidden + (M - 1) * v.ldh + v.K)};
         p.producer[0] = p.producer[1] = -1;
         p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(xr, {}, p.producer);
-        phases.push_back(p);
+        // When K is chunked every tile of a workgroup keeps a running sum in LDS.  If the vocabulary's share of
+        // tiles does not fit beside the activations, the phase is split into phases over tile ranges that do:
+        // same matrix and scales, tile numbering shifted (tile_begin < 0), the running argmax carried in
+        // registers from one to the next; the later ones find their input already there.
+        {
+            int xs = 0, sc = 0, ac = 0;
+            SeqPhase probe = p;
+            plan_phase(probe, MP, w16, a8, G, xs, sc, ac);
+            const int stage_all = 2 * kSeqWaves * NB * 1024;
+            int part = p.T;
+            if (xs + sc + stage_all + ac > kMaxLds) {
+                const int per_tile = kTileRows * 2 + NB * 1024;
+                const int room = kMaxLds - xs - stage_all - 256 - 64;
+                const int tpw = room / per_tile;
+                if (tpw < 1) return QUASAR_ERR_SHAPE;
+                part = tpw * G;
+            }
+            const int nsub = (p.T + part - 1) / part;
+            if (nsub > kSeqExtraPhases + 1) return QUASAR_ERR_SHAPE;
+            const int T_all = p.T;
+            for (int j = 0; j < nsub; ++j) {
+                SeqPhase q = p;
+                q.T = T_all - j * part < part ? T_all - j * part : part;
+                q.seg[0].tile_begin = -j * part;
+                if (j > 0) { q.wait = SEQ_WAIT_NONE; q.producer[0] = q.producer[1] = -1; }
+                phases.push_back(q);
+            }
+        }
     }
     for (SeqPhase &p : phases) {
         if (p.wait != SEQ_WAIT_FLAGS) { p.producer[0] = p.producer[1] = -1; continue; }
@@ -967,7 +998,7 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
     if (lds > kMaxLds) return QUASAR_ERR_SHAPE;
     if (hipMemcpy(plan_device, phases.data(), phases.size() * sizeof(SeqPhase), hipMemcpyHostToDevice) != hipSuccess)
         return QUASAR_ERR_HIP;
-    if (hipMemset(static_cast<unsigned char *>(plan_device) + (size_t)(n_linears + 1) * sizeof(SeqPhase), 0,
+    if (hipMemset(static_cast<unsigned char *>(plan_device) + seq_table_phases(n_linears) * sizeof(SeqPhase), 0,
                   kSeqZeroBytes) != hipSuccess)
         return QUASAR_ERR_HIP;
     // epoch and completion flags start from zero (the first launch runs in epoch 1)
@@ -1029,7 +1060,7 @@ static int sequence_run_impl(const quasar_sequence *seq, const void *plan_device
         sp.stamps = reinterpret_cast<unsigned long long *>(stamps);
     }
     sp.zeros = reinterpret_cast<const u32x4 *>(static_cast<const unsigned char *>(plan_device) +
-                                               (size_t)(h.n_linears + 1) * sizeof(SeqPhase));
+                                               seq_table_phases(h.n_linears) * sizeof(SeqPhase));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (h.roles == 2) {
         if (h.MP != 8) return QUASAR_ERR_SHAPE;

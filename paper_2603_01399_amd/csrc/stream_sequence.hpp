@@ -38,7 +38,8 @@ struct SeqSeg {
     const uint16_t *scales;  // [N] (nullptr for bf16 weights)
     uint16_t *y;             // [M, N] output, row stride ldy
     long long ldy;
-    int tile_begin;          // index of the segment's first tile inside the phase
+    int tile_begin;          // index of the segment's first tile inside the phase (minus the tiles that earlier phases
+                             // of a split vocabulary took: tile t of the phase is tile t - tile_begin of the matrix)
     int N;
 };
 
@@ -612,7 +613,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
             if (i >= 0 && i < ntiles * (kTileRows / 2)) {
                 const int t = t0 + (i >> 3);
                 const uint16_t *base = P.seg[0].scales;
-                int tb = 0;
+                int tb = P.seg[0].tile_begin;   // (negative for the later parts of a vocabulary split over tile ranges)
                 if (P.nseg > 1 && t >= P.seg[1].tile_begin) { base = P.seg[1].scales; tb = P.seg[1].tile_begin; }
                 if (P.nseg > 2 && t >= P.seg[2].tile_begin) { base = P.seg[2].scales; tb = P.seg[2].tile_begin; }
                 if (P.nseg > 3 && t >= P.seg[3].tile_begin) { base = P.seg[3].scales; tb = P.seg[3].tile_begin; }

@@ -384,3 +384,93 @@ def test_whole_step_launch_with_qwen3_32b_layer_shapes(qb, M):
         err = ref.rel_maxabs_err(ref.bf16_bits_to_f64(bf16_to_host(bufs[li][name])), ref.w8_linear(xin[name], q_ref, s_ref))
         print("32B layer", name, "M", M, "rel err", err, flush=True)
         assert err <= TOL and err <= 4e-3
+
+
+@pytest.mark.timeout(900)
+def test_whole_step_launch_m32_splits_the_vocabulary_phase(qb):
+    """M = 32 with the larger model's hidden size and the full vocabulary: K = 5120 takes several LDS chunks, and
+    the per-tile running sums of a workgroup's 38 vocabulary tiles do not fit beside them, so the vocabulary is
+    planned as several phases over tile ranges with the running argmax carried across.  One decoder layer in
+    front of it (its down_proj output is the hidden state).  The vocabulary matrix is planted on the hidden
+    state that the chain produces, so the argmax of every position and the accepted length are known exactly;
+    everything also equals the single calls bit for bit."""
+    print("32B-shaped layer + full vocabulary, M 32", flush=True)
+    shapes = synth.QWEN3_32B_LAYER
+    M, H, V = 32, 5120, synth.QWEN3_VOCAB
+    dev = torch.device("cuda")
+    lin = []
+    for i, (name, K, N) in enumerate(shapes):
+        w = synth.normal_weights(N, K, seed=synth.seed_for(17, 0, i), std=1.0 / np.sqrt(K))
+        wq, sc = qb.quantize_weights(f32_to_dev(w))
+        del w
+        lin.append((name, K, N, wq, sc))
+    x0 = bf16_to_dev(synth.activations_bf16(M, H, seed=synth.seed_for(17, 1, M)))
+
+    def buffers():
+        return {n: torch.zeros((M, N), dtype=torch.bfloat16, device=dev) for n, _, N in shapes}
+
+    def linears(b):
+        src = {"q_proj": x0, "k_proj": x0, "v_proj": x0, "o_proj": b["q_proj"], "gate_proj": b["o_proj"],
+               "up_proj": b["o_proj"], "down_proj": b["gate_proj"]}
+        return [(src[name], wq, sc, N, b[name]) for name, K, N, wq, sc in lin]
+
+    ref_b = buffers()
+    for x, wq, sc, N, y in linears(ref_b):
+        qb.w8_linear(x, wq, sc, N, y)
+    torch.cuda.synchronize()
+    hidden = ref_b["down_proj"].float()                                   # what the vocabulary phase will read
+    assert torch.isfinite(hidden).all() and float(hidden.abs().max()) > 0
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.seed_for(17, 2, 0))
+    wv = torch.randn((V, H), generator=gen, device=dev, dtype=torch.float32) * 0.02
+    rand_q, rand_s = qb.quantize_weights(wv)                              # the same matrix before anything is planted
+    rng = np.random.Generator(np.random.Philox(synth.seed_for(17, 3, 0)))
+    t = rng.choice(V, size=M, replace=False).astype(np.int64)
+    t[0], t[1] = 0, V - 1                                                  # first and last row of the matrix
+    # row t_m raised along h_m: its logit at position m is ~ c_m, far above the ~ 0.02 |h_m| * 5 of any other row
+    norms = (hidden * hidden).sum(dim=1)
+    c = 40.0 * 0.02 * norms.sqrt()
+    wv[torch.from_numpy(t).to(dev)] += (c / norms)[:, None] * hidden
+    head_q, head_s = qb.quantize_weights(wv)
+    del wv
+    j = 19
+    d = t[:-1].astype(np.int32).copy()                                     # candidate i is checked against position i
+    d[j] = (d[j] + 1) % V                                                  # first mismatch at candidate j
+    draft = i32_to_dev(d)
+
+    b = buffers()
+    am = torch.full((M,), -1, dtype=torch.int32, device=dev)
+    acc = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    seq = qb.Sequence(linears(b), verify=(b["down_proj"], head_q, head_s, V, draft, am, acc))
+    print("   phases", seq.nphases, flush=True)
+    assert seq.nphases > 4 + 1 and seq.n_barriers == 0                     # the vocabulary took more than one phase
+    for _ in range(2):
+        seq.run()
+    torch.cuda.synchronize()
+    assert not seq.timed_out()
+    for name, _, _ in shapes:
+        assert torch.equal(b[name].view(torch.int16), ref_b[name].view(torch.int16)), name
+    assert np.array_equal(am.cpu().numpy(), t)
+    assert int(acc.cpu()[0]) == j
+    am2, acc2 = qb.lmhead_verify(ref_b["down_proj"], head_q, head_s, V, draft, qb.make_workspace(M, V, H))
+    torch.cuda.synchronize()
+    assert torch.equal(am, am2) and torch.equal(acc, acc2)
+    # the same with the unplanted matrix, where the winning margins are small: every tile of every part has to
+    # come out with its own row scale (planted rows win whatever scale they get) - against the single call and
+    # against the maximum of the logits recomputed from the unpacked codes
+    am3 = torch.full((M,), -1, dtype=torch.int32, device=dev)
+    acc3 = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    b3 = buffers()
+    seq3 = qb.Sequence(linears(b3), verify=(b3["down_proj"], rand_q, rand_s, V, draft, am3, acc3))
+    assert seq3.nphases == seq.nphases
+    seq3.run()
+    torch.cuda.synchronize()
+    assert not seq3.timed_out()
+    am4, acc4 = qb.lmhead_verify(ref_b["down_proj"], rand_q, rand_s, V, draft, qb.make_workspace(M, V, H))
+    torch.cuda.synchronize()
+    assert torch.equal(am3, am4) and torch.equal(acc3, acc4)
+    logits = (ref_b["down_proj"].float() @ qb.unpack_weights(rand_q, V, H).float().t()) * rand_s.float()[None, :]
+    top2 = logits.topk(2, dim=1)
+    clear = (top2.values[:, 0] - top2.values[:, 1]) > 1e-3 * top2.values[:, 0].abs()
+    assert int(clear.sum()) >= M // 2
+    assert torch.equal(am3[clear].long(), top2.indices[clear, 0])
