@@ -907,8 +907,9 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
         p.wait = phases.empty() ? SEQ_WAIT_NONE : classify(xr, {}, p.producer);
         // When K is chunked every tile of a workgroup keeps a running sum in LDS.  If the vocabulary's share of
         // tiles does not fit beside the activations, the phase is split into phases over tile ranges that do:
-        // same matrix and scales, tile numbering shifted (tile_begin < 0), the running argmax carried in
-        // registers from one to the next; the later ones find their input already there.
+        // weight and scale pointers advanced to the range, the row indices of the argmax shifted by as much,
+        // the running argmax carried in registers from one to the next; the later ones find their input already
+        // there.
         {
             int xs = 0, sc = 0, ac = 0;
             SeqPhase probe = p;
@@ -928,7 +929,9 @@ static int sequence_prepare_impl(const quasar_linear_desc *linears, int64_t n_li
             for (int j = 0; j < nsub; ++j) {
                 SeqPhase q = p;
                 q.T = T_all - j * part < part ? T_all - j * part : part;
-                q.seg[0].tile_begin = -j * part;
+                q.tile_shift = j * part;
+                q.seg[0].w = p.seg[0].w + (size_t)j * part * p.S * 64;
+                if (p.seg[0].scales) q.seg[0].scales = p.seg[0].scales + (size_t)j * part * kTileRows;
                 if (j > 0) { q.wait = SEQ_WAIT_NONE; q.producer[0] = q.producer[1] = -1; }
                 phases.push_back(q);
             }

@@ -38,8 +38,7 @@ struct SeqSeg {
     const uint16_t *scales;  // [N] (nullptr for bf16 weights)
     uint16_t *y;             // [M, N] output, row stride ldy
     long long ldy;
-    int tile_begin;          // index of the segment's first tile inside the phase (minus the tiles that earlier phases
-                             // of a split vocabulary took: tile t of the phase is tile t - tile_begin of the matrix)
+    int tile_begin;          // index of the segment's first tile inside the phase
     int N;
 };
 
@@ -64,6 +63,8 @@ struct SeqPhase {
     const float *smooth;     // W8A8: per-channel smoothing factors of the input ([K], nullptr: none)
     int xs_bytes;            // LDS bytes this phase reserves for activations (a chunk; W8A8: codes, and the parked bf16)
     int sc_bytes;            // LDS bytes for its row scales (+ 256 for the per-token step sizes of the W8A8 form)
+    int tile_shift;          // vocabulary split over tile ranges: tiles of the matrix in front of this phase's first (its
+                             // weight and scale pointers start there; only the row indices of the argmax need the shift)
 };
 
 typedef const __attribute__((address_space(4))) SeqPhase *const_phase_ptr;   // scalar (constant) loads
@@ -334,7 +335,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
         const int s = seg_of(P, c_t0 + c_tl);
         c_y = P.seg[s].y;
         c_ldy = P.seg[s].ldy;
-        c_tb = P.seg[s].tile_begin;
+        c_tb = P.seg[s].tile_begin - P.tile_shift;
         c_seg_end = (s + 1 < P.nseg) ? P.seg[s + 1].tile_begin : P.T;
     };
     unsigned int barriers_done = 0;
@@ -613,7 +614,7 @@ __global__ __launch_bounds__(NW * 64, ROLES == 2 ? 4 : 1) void stream_sequence_k
             if (i >= 0 && i < ntiles * (kTileRows / 2)) {
                 const int t = t0 + (i >> 3);
                 const uint16_t *base = P.seg[0].scales;
-                int tb = P.seg[0].tile_begin;   // (negative for the later parts of a vocabulary split over tile ranges)
+                int tb = 0;
                 if (P.nseg > 1 && t >= P.seg[1].tile_begin) { base = P.seg[1].scales; tb = P.seg[1].tile_begin; }
                 if (P.nseg > 2 && t >= P.seg[2].tile_begin) { base = P.seg[2].scales; tb = P.seg[2].tile_begin; }
                 if (P.nseg > 3 && t >= P.seg[3].tile_begin) { base = P.seg[3].scales; tb = P.seg[3].tile_begin; }
